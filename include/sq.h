@@ -1,0 +1,152 @@
+/*
+ * libsq — SQ-format linear layer on one AMD MI355X (gfx950).  C ABI.
+ *
+ * The layer (paper "SQ-format: A Unified Sparse-Quantized Hardware-friendly Data Format
+ * for LLMs"): an activation matrix X [M, K] (bf16) is put into SQ-format (Section 3.1,
+ * Eq. (1)): every row is cut into banks of `bank` contiguous channels; in each bank
+ * `topk` channels are kept as INT8 ("high") and the others as INT4 ("low"); a mask records
+ * which.  The high channels are either the per-token largest magnitudes of the bank (dynamic,
+ * Sections 3.2.2 and 4.3) or fixed for all tokens by a calibrated channel mask (static,
+ * Algorithm 2).  The other operand is a plain INT4 weight matrix with one scale per output
+ * channel (Section 3.1: only one operand is in SQ-format).  The product is evaluated as two
+ * integer products split by the mask (Section 3.3) and dequantised:
+ *
+ *     acc_lo[m,n] = sum_j      D_lo[m,j] * Wq[n,j]          (INT4 x INT4 -> INT32)
+ *     acc_hi[m,n] = sum_{j hi} S_hi[m,j] * Wq[n,j]          (INT8 x INT4 -> INT32)
+ *     Y[m,n]      = (acc_lo * s_lo[m] + acc_hi * s_hi[m]) * s_w[n]
+ *
+ * General rules
+ *   - Every data pointer is a DEVICE pointer owned by the caller unless it says "host".
+ *     The library never allocates, frees or synchronises: each call checks its arguments,
+ *     enqueues kernels on `stream` (a hipStream_t passed as void*; NULL = default stream)
+ *     and returns.  Structs are read on the host during the call only.
+ *   - Return value: SQ_OK (0) or a negative sq_status.  Invalid arguments never launch anything.
+ *   - Data pointers must be 16-byte aligned and leading dimensions must keep rows 16-byte aligned.
+ *   - Activations must be finite; NaN/Inf give unspecified codes.  A row part whose largest
+ *     magnitude is subnormal gives unspecified codes.
+ *   - No global state, no environment variables; calls on different streams are independent
+ *     as long as their buffers (workspace included) are distinct.
+ */
+#ifndef SQ_H_
+#define SQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SQ_OK = 0,
+  SQ_ERR_NULL = -1,        /* a required pointer is NULL */
+  SQ_ERR_SHAPE = -2,       /* M, K, N <= 0; K % bank; K % 64; leading dimension too small; K too large */
+  SQ_ERR_UNSUPPORTED = -3, /* bank / topk / mode / out_dtype outside the supported set; static mode without a mask */
+  SQ_ERR_ALIGN = -4,       /* pointer or leading dimension breaks the 16-byte alignment rule */
+  SQ_ERR_LAUNCH = -5,      /* the HIP runtime refused a launch */
+  SQ_ERR_MASK = -6,        /* (prepack, host check) a bank of the static mask does not hold exactly topk bits */
+  SQ_ERR_WORKSPACE = -7    /* workspace NULL or smaller than sq_workspace_bytes() */
+} sq_status;
+
+enum { SQ_DYNAMIC = 0, SQ_STATIC = 1 };
+enum { SQ_OUT_F32 = 0, SQ_OUT_BF16 = 1 };
+
+/* Problem description.  Section 4.1 writes a setting as B-(h_high/h_low)-s: here B = bank,
+ * h_high/h_low = 8/4, s = 1 - topk/bank. */
+typedef struct {
+  int32_t M, K, N;   /* tokens, input channels, output channels.  K % bank == 0, K % 64 == 0, K <= 131072 */
+  int32_t bank;      /* 32, 64 or 128 */
+  int32_t topk;      /* high-precision channels per bank, 1 <= topk <= bank/2 and topk <= 32 */
+  int32_t mode;      /* SQ_DYNAMIC or SQ_STATIC */
+  int32_t out_dtype; /* SQ_OUT_F32 or SQ_OUT_BF16 */
+} sq_params;
+
+/* An activation matrix in SQ-format: ([X_quant], [S_quant], [m]) of Eq. (1). */
+typedef struct {
+  uint8_t *d_lo;    /* [M, K/2]  low part: INT4 two's complement in [-7, 7], channel 2i in bits 0-3 and
+                       2i+1 in bits 4-7 of byte i; 0 at high positions */
+  int8_t *hi_val;   /* [M, K/bank, topk]  high part: INT8 in [-127, 127], ascending channel order inside the bank */
+  uint32_t *mask;   /* dynamic: [M, K/32] written by sq_encode; static: [K/32], the caller's channel mask (read only).
+                       bit (j % 32) of word j/32 set <=> channel j is high precision */
+  float *scale_lo;  /* [M] per-token scale of the low part  (largest low magnitude / 7) */
+  float *scale_hi;  /* [M] per-token scale of the high part (largest high magnitude / 127) */
+} sq_act;
+
+/* Plain INT4 weights with one fp32 scale per output channel. */
+typedef struct {
+  const uint8_t *wq;      /* [N, K/2]  same nibble order as d_lo, values in [-8, 7] */
+  const float *scale;     /* [N] */
+  const void *prepacked;  /* static mode: output of sq_weight_prepack (required); dynamic mode: ignored, may be NULL */
+} sq_weight;
+
+/* Byte sizes of the four arrays of an sq_act for these parameters (scales: M floats each).
+ * Returns the total; any out pointer may be NULL.  Returns 0 if the parameters are invalid. */
+size_t sq_act_bytes(const sq_params *p, size_t *d_lo, size_t *hi_val, size_t *mask, size_t *scale);
+
+/* Bytes of device workspace sq_gemm needs (dynamic: the zero-padded INT8 image of the high
+ * part, M*K bytes; static: 0 -> returns 16 so that a valid pointer can always be passed). */
+size_t sq_gemm_workspace_bytes(const sq_params *p);
+
+/* Bytes of device workspace sq_linear needs: an sq_act plus sq_gemm's workspace. */
+size_t sq_linear_workspace_bytes(const sq_params *p);
+
+/* Bytes of the prepacked weight image for the static mode (0 in dynamic mode). */
+size_t sq_weight_prepack_bytes(const sq_params *p);
+
+/*
+ * Static mode only (Algorithm 2, last step: the weights are reordered by the mask so that the
+ * kernels only select and gather on the activation side, Section 3.3): gathers the weight
+ * columns of the high channels into a compact [N, (K/bank)*topk / 2] INT4 image.
+ *   wq               device [N, K/2]
+ *   static_mask_host HOST   [K/32]; checked here: every bank must hold exactly topk bits (SQ_ERR_MASK)
+ *   static_mask      device [K/32], same content
+ *   out              device, sq_weight_prepack_bytes(p) bytes
+ */
+int sq_weight_prepack(const sq_params *p, const uint8_t *wq, const uint32_t *static_mask_host,
+                      const uint32_t *static_mask, void *out, void *stream);
+
+/*
+ * X -> SQ-format (Eq. (1); selection rule of Sections 3.2.2 / 4.3 or Algorithm 2's mask).
+ *   x_bf16       device [M, ldx] bf16 bit patterns, ldx >= K (elements)
+ *   static_mask  device [K/32] in static mode (also stored by the caller in out->mask), NULL in dynamic mode
+ *   out          arrays sized by sq_act_bytes; in static mode out->mask is not written
+ * Ties in magnitude go to the lower channel; codes are round-half-even of x * (Q / amax).
+ */
+int sq_encode(const sq_params *p, const uint16_t *x_bf16, int64_t ldx, const uint32_t *static_mask,
+              const sq_act *out, void *stream);
+
+/*
+ * The two integer products of Section 3.3 and the dequantising epilogue.
+ *   a           encoded activations (static mode: a->mask is the [K/32] channel mask)
+ *   w           weights
+ *   y           device [M, ldy] fp32 or bf16 (p->out_dtype), ldy >= N (elements)
+ *   acc_lo_dbg  optional device [M, N] int32: the exact low-part accumulators
+ *   acc_hi_dbg  optional device [M, N] int32: the exact high-part accumulators
+ *   workspace   device, sq_gemm_workspace_bytes(p) bytes, contents destroyed
+ */
+int sq_gemm(const sq_params *p, const sq_act *a, const sq_weight *w, void *y, int64_t ldy,
+            int32_t *acc_lo_dbg, int32_t *acc_hi_dbg, void *workspace, size_t workspace_bytes, void *stream);
+
+/* sq_encode into the workspace followed by sq_gemm: Y = SQ(X) . W^T, everything on `stream`. */
+int sq_linear(const sq_params *p, const uint16_t *x_bf16, int64_t ldx, const uint32_t *static_mask,
+              const sq_weight *w, void *y, int64_t ldy, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Reference point for the benchmark: a plain per-token W4A8 layer (no SQ split) on the same
+ * INT8 matrix-core kernel, which is what Section 4.2 says W4A8 falls back to on GPUs.
+ * sq_dense_w4a8_prepack reorders the nibbles of wq [N, K/2] into `out` (N*K/2 bytes) for it; the
+ * result goes into w->prepacked.  a_i8 device [M, K] INT8 codes, a_scale device [M];
+ * Y = (A.Wq^T) * a_scale[m] * s_w[n].  Only M, K, N and out_dtype of `p` are read. */
+int sq_dense_w4a8_prepack(const sq_params *p, const uint8_t *wq, void *out, void *stream);
+int sq_dense_w4a8_gemm(const sq_params *p, const int8_t *a_i8, const float *a_scale, const sq_weight *w,
+                       void *y, int64_t ldy, void *stream);
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *sq_status_string(int status);
+
+/* Library version, "major.minor". */
+const char *sq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SQ_H_ */

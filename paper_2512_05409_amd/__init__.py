@@ -1,0 +1,207 @@
+"""Python binding of libsq (the SQ-format linear layer for MI355X).
+
+Argument marshalling only: every function here has the name and the meaning of the C entry
+point declared in ``include/sq.h`` and passes device pointers of torch tensors straight
+through.  No arithmetic of the method happens in Python, and there is no fallback: if the
+HIP library is missing or no GPU is present the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libsq.so")
+
+SQ_DYNAMIC, SQ_STATIC = 0, 1
+SQ_OUT_F32, SQ_OUT_BF16 = 0, 1
+
+EXPORTS = (
+    "sq_act_bytes", "sq_gemm_workspace_bytes", "sq_linear_workspace_bytes", "sq_weight_prepack_bytes",
+    "sq_weight_prepack", "sq_encode", "sq_gemm", "sq_linear", "sq_dense_w4a8_prepack", "sq_dense_w4a8_gemm",
+    "sq_status_string", "sq_version",
+)
+
+
+class SqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+class sq_params(ctypes.Structure):
+    _fields_ = [("M", ctypes.c_int32), ("K", ctypes.c_int32), ("N", ctypes.c_int32), ("bank", ctypes.c_int32),
+                ("topk", ctypes.c_int32), ("mode", ctypes.c_int32), ("out_dtype", ctypes.c_int32)]
+
+
+class sq_act(ctypes.Structure):
+    _fields_ = [("d_lo", ctypes.c_void_p), ("hi_val", ctypes.c_void_p), ("mask", ctypes.c_void_p),
+                ("scale_lo", ctypes.c_void_p), ("scale_hi", ctypes.c_void_p)]
+
+
+class sq_weight(ctypes.Structure):
+    _fields_ = [("wq", ctypes.c_void_p), ("scale", ctypes.c_void_p), ("prepacked", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libsq.so (built in-tree by ``paper_2512_05409_amd.build``); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2512_05409_amd.build` (needs hipcc)")
+        L = ctypes.CDLL(LIB_PATH)
+        P, vp, sz, i64 = ctypes.POINTER, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int64
+        L.sq_act_bytes.argtypes = [P(sq_params), P(sz), P(sz), P(sz), P(sz)]
+        L.sq_act_bytes.restype = sz
+        for f in (L.sq_gemm_workspace_bytes, L.sq_linear_workspace_bytes, L.sq_weight_prepack_bytes):
+            f.argtypes = [P(sq_params)]
+            f.restype = sz
+        L.sq_weight_prepack.argtypes = [P(sq_params), vp, vp, vp, vp, vp]
+        L.sq_encode.argtypes = [P(sq_params), vp, i64, vp, P(sq_act), vp]
+        L.sq_gemm.argtypes = [P(sq_params), P(sq_act), P(sq_weight), vp, i64, vp, vp, vp, sz, vp]
+        L.sq_linear.argtypes = [P(sq_params), vp, i64, vp, P(sq_weight), vp, i64, vp, sz, vp]
+        L.sq_dense_w4a8_prepack.argtypes = [P(sq_params), vp, vp, vp]
+        L.sq_dense_w4a8_gemm.argtypes = [P(sq_params), vp, vp, P(sq_weight), vp, i64, vp]
+        for f in (L.sq_weight_prepack, L.sq_encode, L.sq_gemm, L.sq_linear, L.sq_dense_w4a8_prepack,
+                  L.sq_dense_w4a8_gemm):
+            f.restype = ctypes.c_int
+        L.sq_status_string.argtypes = [ctypes.c_int]
+        L.sq_status_string.restype = ctypes.c_char_p
+        L.sq_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().sq_status_string(int(status)).decode()
+
+
+def version() -> str:
+    return lib().sq_version().decode()
+
+
+def params(M: int, K: int, N: int, bank: int = 64, topk: int = 8, mode: int = SQ_DYNAMIC,
+           out_dtype: int = SQ_OUT_BF16) -> sq_params:
+    return sq_params(int(M), int(K), int(N), int(bank), int(topk), int(mode), int(out_dtype))
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise SqError(rc, where)
+
+
+def _ptr(t) -> Optional[int]:
+    """Device address of a torch tensor (None -> NULL)."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("libsq takes device tensors")
+    if not t.is_contiguous():
+        raise ValueError("libsq takes contiguous tensors")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    import torch
+
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+@dataclass
+class ActBytes:
+    d_lo: int
+    hi_val: int
+    mask: int
+    scale: int
+    total: int
+
+
+def sq_act_bytes(p: sq_params) -> ActBytes:
+    a, b, c, d = (ctypes.c_size_t() for _ in range(4))
+    tot = lib().sq_act_bytes(ctypes.byref(p), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(d))
+    if tot == 0:
+        raise SqError(-3, "sq_act_bytes (invalid parameters)")
+    return ActBytes(a.value, b.value, c.value, d.value, tot)
+
+
+def sq_gemm_workspace_bytes(p: sq_params) -> int:
+    return int(lib().sq_gemm_workspace_bytes(ctypes.byref(p)))
+
+
+def sq_linear_workspace_bytes(p: sq_params) -> int:
+    return int(lib().sq_linear_workspace_bytes(ctypes.byref(p)))
+
+
+def sq_weight_prepack_bytes(p: sq_params) -> int:
+    return int(lib().sq_weight_prepack_bytes(ctypes.byref(p)))
+
+
+class Act:
+    """Device buffers of one SQ-format activation matrix (torch tensors, caller-visible)."""
+
+    def __init__(self, p: sq_params, device="cuda", static_mask=None):
+        import torch
+
+        nb = sq_act_bytes(p)
+        self.p = p
+        self.d_lo = torch.empty(nb.d_lo, dtype=torch.uint8, device=device)
+        self.hi_val = torch.empty(nb.hi_val, dtype=torch.int8, device=device)
+        if p.mode == SQ_DYNAMIC:
+            self.mask = torch.empty(nb.mask // 4, dtype=torch.int32, device=device)
+        else:
+            assert static_mask is not None and static_mask.numel() == p.K // 32
+            self.mask = static_mask
+        self.scale_lo = torch.empty(p.M, dtype=torch.float32, device=device)
+        self.scale_hi = torch.empty(p.M, dtype=torch.float32, device=device)
+
+    def c(self) -> sq_act:
+        return sq_act(_ptr(self.d_lo), _ptr(self.hi_val), _ptr(self.mask), _ptr(self.scale_lo), _ptr(self.scale_hi))
+
+
+def weight(wq, scale, prepacked=None) -> sq_weight:
+    return sq_weight(_ptr(wq), _ptr(scale), _ptr(prepacked))
+
+
+def sq_weight_prepack(p: sq_params, wq, static_mask_host, static_mask, out, stream=None) -> None:
+    """static_mask_host: numpy uint32 [K/32] (host); the rest are device tensors."""
+    import numpy as np
+
+    mh = np.ascontiguousarray(static_mask_host, dtype=np.uint32)
+    _check(lib().sq_weight_prepack(ctypes.byref(p), _ptr(wq), mh.ctypes.data, _ptr(static_mask), _ptr(out),
+                                   _stream(stream)), "sq_weight_prepack")
+
+
+def sq_encode(p: sq_params, x_bf16, out: Act, static_mask=None, ldx: Optional[int] = None, stream=None) -> None:
+    a = out.c()
+    _check(lib().sq_encode(ctypes.byref(p), _ptr(x_bf16), p.K if ldx is None else ldx, _ptr(static_mask),
+                           ctypes.byref(a), _stream(stream)), "sq_encode")
+
+
+def sq_gemm(p: sq_params, a: Act, w: sq_weight, y, workspace, acc_lo_dbg=None, acc_hi_dbg=None,
+            ldy: Optional[int] = None, stream=None) -> None:
+    ac = a.c()
+    _check(lib().sq_gemm(ctypes.byref(p), ctypes.byref(ac), ctypes.byref(w), _ptr(y), p.N if ldy is None else ldy,
+                         _ptr(acc_lo_dbg), _ptr(acc_hi_dbg), _ptr(workspace),
+                         workspace.numel() * workspace.element_size(), _stream(stream)), "sq_gemm")
+
+
+def sq_linear(p: sq_params, x_bf16, w: sq_weight, y, workspace, static_mask=None, ldx: Optional[int] = None,
+              ldy: Optional[int] = None, stream=None) -> None:
+    _check(lib().sq_linear(ctypes.byref(p), _ptr(x_bf16), p.K if ldx is None else ldx, _ptr(static_mask),
+                           ctypes.byref(w), _ptr(y), p.N if ldy is None else ldy, _ptr(workspace),
+                           workspace.numel() * workspace.element_size(), _stream(stream)), "sq_linear")
+
+
+def sq_dense_w4a8_prepack(p: sq_params, wq, out, stream=None) -> None:
+    _check(lib().sq_dense_w4a8_prepack(ctypes.byref(p), _ptr(wq), _ptr(out), _stream(stream)), "sq_dense_w4a8_prepack")
+
+
+def sq_dense_w4a8_gemm(p: sq_params, a_i8, a_scale, w: sq_weight, y, ldy: Optional[int] = None, stream=None) -> None:
+    _check(lib().sq_dense_w4a8_gemm(ctypes.byref(p), _ptr(a_i8), _ptr(a_scale), ctypes.byref(w), _ptr(y),
+                                    p.N if ldy is None else ldy, _stream(stream)), "sq_dense_w4a8_gemm")

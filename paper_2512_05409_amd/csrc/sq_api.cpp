@@ -1,0 +1,258 @@
+// C ABI of libsq: argument checks, workspace carving and kernel dispatch.  No allocation, no
+// synchronisation; every entry point only enqueues work on the caller's stream.
+#include <string.h>
+
+#include "sq_device.h"
+
+namespace {
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+
+int check_params(const sq_params* p) {
+  if (!p) return SQ_ERR_NULL;
+  if (p->M <= 0 || p->K <= 0 || p->N <= 0) return SQ_ERR_SHAPE;
+  if (p->bank != 32 && p->bank != 64 && p->bank != 128) return SQ_ERR_UNSUPPORTED;
+  if (p->K % p->bank || p->K % 64 || p->K > 131072) return SQ_ERR_SHAPE;
+  if (p->K / p->bank > 512) return SQ_ERR_SHAPE;
+  if (p->M > (1 << 22) || p->N > (1 << 24)) return SQ_ERR_SHAPE;
+  if (p->mode != SQ_DYNAMIC && p->mode != SQ_STATIC) return SQ_ERR_UNSUPPORTED;
+  if (p->out_dtype != SQ_OUT_F32 && p->out_dtype != SQ_OUT_BF16) return SQ_ERR_UNSUPPORTED;
+  if (!pow2(p->topk) || p->topk > 32 || p->topk * 2 > p->bank) return SQ_ERR_UNSUPPORTED;
+  if (p->mode == SQ_DYNAMIC && p->topk * 16 < p->bank) return SQ_ERR_UNSUPPORTED;  // s in {1/2,3/4,7/8,15/16}
+  if (p->mode == SQ_STATIC && ((p->K / p->bank) * p->topk) % 32) return SQ_ERR_UNSUPPORTED;
+  return SQ_OK;
+}
+
+inline int k_hi_of(const sq_params* p) { return (p->K / p->bank) * p->topk; }
+
+struct ActLayout {
+  size_t d_lo, hi_val, mask, scale, total;
+};
+ActLayout act_layout(const sq_params* p) {
+  ActLayout l;
+  l.d_lo = static_cast<size_t>(p->M) * (p->K / 2);
+  l.hi_val = static_cast<size_t>(p->M) * k_hi_of(p);
+  l.mask = p->mode == SQ_DYNAMIC ? static_cast<size_t>(p->M) * (p->K / 32) * 4 : static_cast<size_t>(p->K / 32) * 4;
+  l.scale = static_cast<size_t>(p->M) * 4;
+  l.total = l.d_lo + l.hi_val + l.mask + 2 * l.scale;
+  return l;
+}
+
+int check_act(const sq_params* p, const sq_act* a) {
+  if (!a || !a->d_lo || !a->hi_val || !a->mask || !a->scale_lo || !a->scale_hi) return SQ_ERR_NULL;
+  if (!aligned16(a->d_lo) || !aligned16(a->hi_val) || !aligned16(a->mask) || !aligned16(a->scale_lo) ||
+      !aligned16(a->scale_hi))
+    return SQ_ERR_ALIGN;
+  (void)p;
+  return SQ_OK;
+}
+
+int check_weight(const sq_params* p, const sq_weight* w) {
+  if (!w || !w->wq || !w->scale) return SQ_ERR_NULL;
+  if (p->mode == SQ_STATIC && !w->prepacked) return SQ_ERR_NULL;
+  if (!aligned16(w->wq) || !aligned16(w->scale) || (w->prepacked && !aligned16(w->prepacked))) return SQ_ERR_ALIGN;
+  return SQ_OK;
+}
+
+int check_y(const sq_params* p, const void* y, int64_t ldy) {
+  if (!y) return SQ_ERR_NULL;
+  if (ldy < p->N) return SQ_ERR_SHAPE;
+  if (!aligned16(y)) return SQ_ERR_ALIGN;
+  return SQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t sq_act_bytes(const sq_params* p, size_t* d_lo, size_t* hi_val, size_t* mask, size_t* scale) {
+  if (check_params(p) != SQ_OK) return 0;
+  const ActLayout l = act_layout(p);
+  if (d_lo) *d_lo = l.d_lo;
+  if (hi_val) *hi_val = l.hi_val;
+  if (mask) *mask = l.mask;
+  if (scale) *scale = l.scale;
+  return l.total;
+}
+
+size_t sq_gemm_workspace_bytes(const sq_params* p) {
+  if (check_params(p) != SQ_OK) return 0;
+  if (p->mode == SQ_DYNAMIC) return align_up(static_cast<size_t>(p->M) * p->K, 256);
+  return 16;
+}
+
+size_t sq_linear_workspace_bytes(const sq_params* p) {
+  if (check_params(p) != SQ_OK) return 0;
+  const ActLayout l = act_layout(p);
+  size_t t = align_up(l.d_lo, 256) + align_up(l.hi_val, 256) + 2 * align_up(l.scale, 256);
+  if (p->mode == SQ_DYNAMIC) t += align_up(l.mask, 256);
+  return t + sq_gemm_workspace_bytes(p);
+}
+
+size_t sq_weight_prepack_bytes(const sq_params* p) {
+  if (check_params(p) != SQ_OK || p->mode != SQ_STATIC) return 0;
+  return static_cast<size_t>(p->N) * (k_hi_of(p) / 2);
+}
+
+int sq_weight_prepack(const sq_params* p, const uint8_t* wq, const uint32_t* static_mask_host,
+                      const uint32_t* static_mask, void* out, void* stream) {
+  int rc = check_params(p);
+  if (rc != SQ_OK) return rc;
+  if (p->mode != SQ_STATIC) return SQ_ERR_UNSUPPORTED;
+  if (!wq || !static_mask_host || !static_mask || !out) return SQ_ERR_NULL;
+  if (!aligned16(wq) || !aligned16(out)) return SQ_ERR_ALIGN;
+  for (int g = 0; g < p->K / p->bank; ++g) {
+    int c = 0;
+    for (int i = 0; i < p->bank; ++i) {
+      const int j = g * p->bank + i;
+      c += (static_mask_host[j >> 5] >> (j & 31)) & 1u;
+    }
+    if (c != p->topk) return SQ_ERR_MASK;
+  }
+  return sq::launch_weight_prepack(p->N, p->K, p->bank, p->topk, k_hi_of(p), wq, static_mask,
+                                   static_cast<uint8_t*>(out), static_cast<hipStream_t>(stream));
+}
+
+int sq_encode(const sq_params* p, const uint16_t* x_bf16, int64_t ldx, const uint32_t* static_mask, const sq_act* out,
+              void* stream) {
+  int rc = check_params(p);
+  if (rc != SQ_OK) return rc;
+  if (!x_bf16) return SQ_ERR_NULL;
+  if (ldx < p->K) return SQ_ERR_SHAPE;
+  if (!aligned16(x_bf16) || (ldx % 8)) return SQ_ERR_ALIGN;
+  if (p->mode == SQ_STATIC) {
+    if (!static_mask) return SQ_ERR_UNSUPPORTED;
+    if (!out || !out->d_lo || !out->hi_val || !out->scale_lo || !out->scale_hi) return SQ_ERR_NULL;
+    if (!aligned16(out->d_lo) || !aligned16(out->hi_val) || !aligned16(static_mask)) return SQ_ERR_ALIGN;
+    return sq::launch_encode_static(*p, x_bf16, ldx, static_mask, *out, static_cast<hipStream_t>(stream));
+  }
+  rc = check_act(p, out);
+  if (rc != SQ_OK) return rc;
+  return sq::launch_encode_dynamic(*p, x_bf16, ldx, *out, static_cast<hipStream_t>(stream));
+}
+
+int sq_gemm(const sq_params* p, const sq_act* a, const sq_weight* w, void* y, int64_t ldy, int32_t* acc_lo_dbg,
+            int32_t* acc_hi_dbg, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_params(p);
+  if (rc != SQ_OK) return rc;
+  if ((rc = check_act(p, a)) != SQ_OK) return rc;
+  if ((rc = check_weight(p, w)) != SQ_OK) return rc;
+  if ((rc = check_y(p, y, ldy)) != SQ_OK) return rc;
+  if (!workspace || workspace_bytes < sq_gemm_workspace_bytes(p)) return SQ_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return SQ_ERR_ALIGN;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  sq::GemmArgs g;
+  memset(&g, 0, sizeof g);
+  g.M = p->M;
+  g.N = p->N;
+  g.K = p->K;
+  g.a_lo = a->d_lo;
+  g.wq = w->wq;
+  g.s_lo = a->scale_lo;
+  g.s_hi = a->scale_hi;
+  g.s_w = w->scale;
+  g.y = y;
+  g.ldy = ldy;
+  g.out_bf16 = p->out_dtype == SQ_OUT_BF16;
+  g.acc_lo_dbg = acc_lo_dbg;
+  g.acc_hi_dbg = acc_hi_dbg;
+  if (p->mode == SQ_DYNAMIC) {
+    rc = sq::launch_expand_hi(*p, *a, static_cast<int8_t*>(workspace), st);
+    if (rc != SQ_OK) return rc;
+    g.a_hi_dense = static_cast<const int8_t*>(workspace);
+  } else {
+    g.K_hi = k_hi_of(p);
+    g.a_hi_compact = a->hi_val;
+    g.lda_hi_compact = g.K_hi;
+    g.w_hi = static_cast<const uint8_t*>(w->prepacked);
+  }
+  return sq::launch_gemm(g, st);
+}
+
+int sq_linear(const sq_params* p, const uint16_t* x_bf16, int64_t ldx, const uint32_t* static_mask, const sq_weight* w,
+              void* y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_params(p);
+  if (rc != SQ_OK) return rc;
+  if (!workspace || workspace_bytes < sq_linear_workspace_bytes(p)) return SQ_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SQ_ERR_ALIGN;
+  if (p->mode == SQ_STATIC && !static_mask) return SQ_ERR_UNSUPPORTED;
+  // checked here so that a bad weight / output argument cannot leave a half-done call behind
+  if ((rc = check_weight(p, w)) != SQ_OK) return rc;
+  if ((rc = check_y(p, y, ldy)) != SQ_OK) return rc;
+  const ActLayout l = act_layout(p);
+  char* ws = static_cast<char*>(workspace);
+  sq_act a;
+  a.d_lo = reinterpret_cast<uint8_t*>(ws);
+  ws += align_up(l.d_lo, 256);
+  a.hi_val = reinterpret_cast<int8_t*>(ws);
+  ws += align_up(l.hi_val, 256);
+  a.scale_lo = reinterpret_cast<float*>(ws);
+  ws += align_up(l.scale, 256);
+  a.scale_hi = reinterpret_cast<float*>(ws);
+  ws += align_up(l.scale, 256);
+  if (p->mode == SQ_DYNAMIC) {
+    a.mask = reinterpret_cast<uint32_t*>(ws);
+    ws += align_up(l.mask, 256);
+  } else {
+    a.mask = const_cast<uint32_t*>(static_mask);
+  }
+  rc = sq_encode(p, x_bf16, ldx, static_mask, &a, stream);
+  if (rc != SQ_OK) return rc;
+  const size_t used = static_cast<size_t>(ws - static_cast<char*>(workspace));
+  return sq_gemm(p, &a, w, y, ldy, nullptr, nullptr, ws, workspace_bytes - used, stream);
+}
+
+int sq_dense_w4a8_prepack(const sq_params* p, const uint8_t* wq, void* out, void* stream) {
+  if (!p || !wq || !out) return SQ_ERR_NULL;
+  if (p->K <= 0 || p->N <= 0 || p->K % 64 || p->K > 131072) return SQ_ERR_SHAPE;
+  if (!aligned16(wq) || !aligned16(out)) return SQ_ERR_ALIGN;
+  return sq::launch_weight_prepack(p->N, p->K, 0, 0, p->K, wq, nullptr, static_cast<uint8_t*>(out),
+                                   static_cast<hipStream_t>(stream));
+}
+
+int sq_dense_w4a8_gemm(const sq_params* p, const int8_t* a_i8, const float* a_scale, const sq_weight* w, void* y,
+                       int64_t ldy, void* stream) {
+  if (!p) return SQ_ERR_NULL;
+  if (p->M <= 0 || p->K <= 0 || p->N <= 0 || p->K % 64 || p->K > 131072) return SQ_ERR_SHAPE;
+  if (p->out_dtype != SQ_OUT_F32 && p->out_dtype != SQ_OUT_BF16) return SQ_ERR_UNSUPPORTED;
+  if (!a_i8 || !a_scale || !w || !w->scale || !w->prepacked) return SQ_ERR_NULL;
+  int rc = check_y(p, y, ldy);
+  if (rc != SQ_OK) return rc;
+  if (!aligned16(a_i8) || !aligned16(w->prepacked)) return SQ_ERR_ALIGN;
+  sq::GemmArgs g;
+  memset(&g, 0, sizeof g);
+  g.M = p->M;
+  g.N = p->N;
+  g.K = p->K;
+  g.K_hi = p->K;
+  g.a_hi_compact = a_i8;
+  g.lda_hi_compact = p->K;
+  g.w_hi = static_cast<const uint8_t*>(w->prepacked);
+  g.s_hi = a_scale;
+  g.s_w = w->scale;
+  g.y = y;
+  g.ldy = ldy;
+  g.out_bf16 = p->out_dtype == SQ_OUT_BF16;
+  return sq::launch_gemm(g, static_cast<hipStream_t>(stream));
+}
+
+const char* sq_status_string(int status) {
+  switch (status) {
+    case SQ_OK: return "SQ_OK";
+    case SQ_ERR_NULL: return "SQ_ERR_NULL: a required pointer is NULL";
+    case SQ_ERR_SHAPE: return "SQ_ERR_SHAPE: bad M/K/N, K not a multiple of bank and 64, or leading dimension too small";
+    case SQ_ERR_UNSUPPORTED: return "SQ_ERR_UNSUPPORTED: bank/topk/mode/out_dtype outside the supported set";
+    case SQ_ERR_ALIGN: return "SQ_ERR_ALIGN: pointer or leading dimension not 16-byte aligned";
+    case SQ_ERR_LAUNCH: return "SQ_ERR_LAUNCH: the HIP runtime refused a launch";
+    case SQ_ERR_MASK: return "SQ_ERR_MASK: a bank of the static mask does not hold exactly topk bits";
+    case SQ_ERR_WORKSPACE: return "SQ_ERR_WORKSPACE: workspace missing or too small";
+    default: return "unknown sq_status";
+  }
+}
+
+const char* sq_version(void) { return "0.1"; }
+
+}  // extern "C"

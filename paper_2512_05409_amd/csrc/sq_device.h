@@ -1,0 +1,46 @@
+// Shared declarations of the libsq kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sq.h"
+
+namespace sq {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// ---- launchers (defined in the .hip files, called by the C ABI in sq_api.hip) ----
+
+// X -> SQ-format, dynamic rule (per-token top-k by magnitude inside each bank).
+int launch_encode_dynamic(const sq_params& p, const uint16_t* x, int64_t ldx, const sq_act& out, hipStream_t st);
+// X -> SQ-format, static rule (channel mask shared by all tokens).
+int launch_encode_static(const sq_params& p, const uint16_t* x, int64_t ldx, const uint32_t* mask, const sq_act& out,
+                         hipStream_t st);
+// (hi_val, mask) -> zero-padded INT8 image [M, K] of the high part, in the K order the GEMM kernel consumes.
+int launch_expand_hi(const sq_params& p, const sq_act& a, int8_t* s_hi_dense, hipStream_t st);
+// Gather of the high channels' weight columns for the static mode.
+int launch_weight_prepack(int N, int K, int bank, int topk, int k_hi_padded, const uint8_t* wq, const uint32_t* mask,
+                          uint8_t* out, hipStream_t st);
+
+struct GemmArgs {
+  int M, N, K;          // K of the low / full pass
+  int K_hi;             // channels of the compact high pass (static / dense-W4A8), multiple of 32
+  const uint8_t* a_lo;  // [M, K/2] packed INT4 (nullptr: no low pass)
+  const int8_t* a_hi_dense;  // dynamic: [M, K] zero-padded INT8 in consumer order (nullptr otherwise)
+  const int8_t* a_hi_compact;  // static: [M, K_hi] INT8 natural order (nullptr otherwise)
+  int64_t lda_hi_compact;      // row stride of a_hi_compact in bytes
+  const uint8_t* wq;           // [N, K/2]
+  const uint8_t* w_hi;         // static: [N, K_hi/2] gathered, half-split nibble order
+  const float* s_lo;           // [M] (nullptr -> treated as 0 contribution)
+  const float* s_hi;           // [M]
+  const float* s_w;            // [N]
+  void* y;
+  int64_t ldy;
+  int out_bf16;
+  int32_t* acc_lo_dbg;
+  int32_t* acc_hi_dbg;
+};
+int launch_gemm(const GemmArgs& g, hipStream_t st);
+
+}  // namespace sq

@@ -1,0 +1,460 @@
+// sq_encode: bf16 activations -> SQ-format (Section 3.1, Eq. (1)); gfx950.
+//
+// One lane owns one bank of one token row and keeps it in registers.  The per-token
+// top-k of the dynamic rule (Sections 3.2.2 / 4.3) is a register-only selection network
+// on keys that are unique inside the bank, so that ties in magnitude resolve to the lower
+// channel without any extra pass:
+//     key = |x| bits (15) << 9  |  (255 - channel_in_bank) << 1  |  sign
+// Groups of k keys are sorted, then merged pairwise keeping only the k largest of each
+// pair; the largest key ever dropped gives the bank's largest low-precision magnitude.
+// The per-token scales need the row maxima of both parts, which the lanes of a row
+// combine through LDS integer atomics (bf16 magnitudes order like integers).
+// The codes are round-half-even of the fp32 product x * (Q/amax): the rounding is done by
+// adding 1.5*2^23, which leaves the two's complement integer in the low mantissa bits.
+#include "sq_device.h"
+
+namespace sq {
+namespace {
+
+constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23
+
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
+
+// Sorts v[0..N) descending (N a power of two); every index is a compile-time constant.
+template <int N>
+__device__ __forceinline__ void bitonic_sort_desc(uint32_t* v) {
+#pragma unroll
+  for (int k = 2; k <= N; k <<= 1) {
+#pragma unroll
+    for (int j = k >> 1; j > 0; j >>= 1) {
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        const int l = i ^ j;
+        if (l > i) {
+          const uint32_t a = v[i], b = v[l];
+          const uint32_t mx = umax(a, b), mn = umin(a, b);
+          const bool desc = (i & k) == 0;
+          v[i] = desc ? mx : mn;
+          v[l] = desc ? mn : mx;
+        }
+      }
+    }
+  }
+}
+
+// v[0..N) is bitonic; sorts it descending.
+template <int N>
+__device__ __forceinline__ void bitonic_merge_desc(uint32_t* v) {
+#pragma unroll
+  for (int j = N >> 1; j > 0; j >>= 1) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int l = i ^ j;
+      if (l > i) {
+        const uint32_t a = v[i], b = v[l];
+        v[i] = umax(a, b);
+        v[l] = umin(a, b);
+      }
+    }
+  }
+}
+
+// fp32 value of a bf16 given as (15-bit magnitude, sign in bit 0 of `sign_lsb`).
+__device__ __forceinline__ float bf16_from_key(uint32_t key) {
+  return __uint_as_float(((key >> 9) << 16) | (key << 31));
+}
+
+// 8 mask bits -> 8 nibbles of all-ones / all-zeros.
+__device__ __forceinline__ uint32_t spread_bits_to_nibbles(uint32_t b8) {
+  uint32_t t = b8 & 0xFFu;
+  t = (t | (t << 12)) & 0x000F000Fu;
+  t = (t | (t << 6)) & 0x03030303u;
+  t = (t | (t << 3)) & 0x11111111u;
+  return (t << 4) - t;  // each 1 -> 0xF
+}
+
+// Low-part codes of 8 consecutive channels (4 packed bf16 pairs) as one dword of nibbles.
+__device__ __forceinline__ uint32_t quant_lo8(const uint32_t* pairs, float inv_lo) {
+  uint32_t acc = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const uint32_t w = pairs[e >> 1];
+    const float xf = __uint_as_float((e & 1) ? (w & 0xFFFF0000u) : (w << 16));
+    const float r = __fadd_rn(__fmul_rn(xf, inv_lo), kRoundMagic);
+    acc |= (__float_as_uint(r) & 0xFu) << (4 * e);
+  }
+  return acc;
+}
+
+template <int N>
+__device__ __forceinline__ void store_bytes(int8_t* dst, const uint32_t* words) {
+  // N bytes (N a power of two <= 32) held in ceil(N/4) dwords; dst is N-byte aligned.
+  if constexpr (N >= 16) {
+#pragma unroll
+    for (int i = 0; i < N / 16; ++i)
+      reinterpret_cast<uint4*>(dst)[i] = make_uint4(words[4 * i], words[4 * i + 1], words[4 * i + 2], words[4 * i + 3]);
+  } else if constexpr (N == 8) {
+    *reinterpret_cast<uint2*>(dst) = make_uint2(words[0], words[1]);
+  } else if constexpr (N == 4) {
+    *reinterpret_cast<uint32_t*>(dst) = words[0];
+  } else if constexpr (N == 2) {
+    *reinterpret_cast<uint16_t*>(dst) = static_cast<uint16_t>(words[0]);
+  } else {
+    *dst = static_cast<int8_t>(words[0]);
+  }
+}
+
+// Thread layout shared by both encoders: a block covers R consecutive rows, lane t owns bank
+// (t % G) of row (t / G); G = K / bank.  amax_sh[2r], amax_sh[2r+1] = row maxima (bf16 magnitude
+// bits) of the high / low part.
+struct BankCoord {
+  int r_local, g;
+  int64_t row;
+  bool active;
+};
+__device__ __forceinline__ BankCoord bank_coord(int G, int R, int M) {
+  BankCoord c;
+  c.r_local = static_cast<int>(threadIdx.x) / G;
+  c.g = static_cast<int>(threadIdx.x) - c.r_local * G;
+  c.row = static_cast<int64_t>(blockIdx.x) * R + c.r_local;
+  c.active = (c.r_local < R) && (c.row < M);
+  return c;
+}
+
+template <int B, int KT, int MAXT>
+__global__ __launch_bounds__(MAXT) void encode_dynamic_kernel(const uint16_t* __restrict__ x, int64_t ldx, int M, int K,
+                                                              int G, int R, uint8_t* __restrict__ d_lo,
+                                                              int8_t* __restrict__ hi_val, uint32_t* __restrict__ mask,
+                                                              float* __restrict__ s_lo, float* __restrict__ s_hi) {
+  static_assert(B % 32 == 0 && KT >= 1 && KT <= 32 && (KT & (KT - 1)) == 0 && B % KT == 0 && B / KT >= 2, "shape");
+  __shared__ uint32_t amax_sh[64];
+  if (threadIdx.x < 64) amax_sh[threadIdx.x] = 0;
+  __syncthreads();
+  const BankCoord c = bank_coord(G, R, M);
+
+  uint32_t xr[B / 2];  // the bank: bf16 pairs, channel 2i in the low half of xr[i]
+  uint32_t top[KT];    // the k largest keys, descending
+  if (c.active) {
+    const uint4* src = reinterpret_cast<const uint4*>(x + c.row * ldx + static_cast<int64_t>(c.g) * B);
+#pragma unroll
+    for (int i = 0; i < B / 8; ++i) {
+      const uint4 v = src[i];
+      xr[4 * i + 0] = v.x;
+      xr[4 * i + 1] = v.y;
+      xr[4 * i + 2] = v.z;
+      xr[4 * i + 3] = v.w;
+    }
+    uint32_t key[B];
+#pragma unroll
+    for (int i = 0; i < B / 2; ++i) {
+      const uint32_t w = xr[i];
+      key[2 * i] = ((w & 0x7FFFu) << 9) | ((255u - 2 * i) << 1) | ((w >> 15) & 1u);
+      key[2 * i + 1] = (((w >> 16) & 0x7FFFu) << 9) | ((255u - (2 * i + 1)) << 1) | (w >> 31);
+    }
+#pragma unroll
+    for (int g0 = 0; g0 < B; g0 += KT) bitonic_sort_desc<KT>(key + g0);
+    uint32_t dropped[KT];
+#pragma unroll
+    for (int i = 0; i < KT; ++i) dropped[i] = 0;
+#pragma unroll
+    for (int width = KT; width < B; width <<= 1) {
+#pragma unroll
+      for (int base = 0; base < B; base += 2 * width) {
+        uint32_t* a = key + base;
+        uint32_t* b = key + base + width;
+#pragma unroll
+        for (int i = 0; i < KT; ++i) {
+          const uint32_t ai = a[i], bj = b[KT - 1 - i];
+          a[i] = umax(ai, bj);
+          dropped[i] = umax(dropped[i], umin(ai, bj));
+        }
+        bitonic_merge_desc<KT>(a);
+      }
+    }
+    uint32_t dmax = dropped[0];
+#pragma unroll
+    for (int i = 1; i < KT; ++i) dmax = umax(dmax, dropped[i]);
+#pragma unroll
+    for (int i = 0; i < KT; ++i) top[i] = key[i];
+    atomicMax(&amax_sh[2 * c.r_local], top[0] >> 9);
+    atomicMax(&amax_sh[2 * c.r_local + 1], dmax >> 9);
+  }
+  __syncthreads();
+  if (!c.active) return;
+
+  const uint32_t ah = amax_sh[2 * c.r_local], al = amax_sh[2 * c.r_local + 1];
+  const float amax_hi = __uint_as_float(ah << 16), amax_lo = __uint_as_float(al << 16);
+  const float inv_hi = ah ? 127.0f / amax_hi : 0.0f;
+  const float inv_lo = al ? 7.0f / amax_lo : 0.0f;
+  if (c.g == 0) {
+    s_hi[c.row] = ah ? amax_hi / 127.0f : 1.0f;
+    s_lo[c.row] = al ? amax_lo / 7.0f : 1.0f;
+  }
+
+  // ---- high part: quantise the k selected values, order them by channel, emit codes and mask ----
+  uint32_t ent[KT];  // channel << 8 | code byte
+  uint32_t mw[B / 32];
+#pragma unroll
+  for (int w = 0; w < B / 32; ++w) mw[w] = 0;
+#pragma unroll
+  for (int t = 0; t < KT; ++t) {
+    const uint32_t key = top[t];
+    const uint32_t ch = 255u - ((key >> 1) & 255u);
+    const float v = __fmul_rn(bf16_from_key(key), inv_hi);
+    const float r = __fadd_rn(v, kRoundMagic);
+    ent[t] = (ch << 8) | (__float_as_uint(r) & 0xFFu);
+#pragma unroll
+    for (int w = 0; w < B / 32; ++w) mw[w] |= ((ch >> 5) == static_cast<uint32_t>(w)) ? (1u << (ch & 31u)) : 0u;
+  }
+  bitonic_sort_desc<KT>(ent);  // descending channel; read back reversed
+  uint32_t hv[(KT + 3) / 4];
+#pragma unroll
+  for (int i = 0; i < (KT + 3) / 4; ++i) hv[i] = 0;
+#pragma unroll
+  for (int t = 0; t < KT; ++t) hv[t / 4] |= (ent[KT - 1 - t] & 0xFFu) << (8 * (t % 4));
+  store_bytes<KT>(hi_val + (c.row * G + c.g) * KT, hv);
+  uint32_t* mdst = mask + c.row * (K / 32) + static_cast<int64_t>(c.g) * (B / 32);
+#pragma unroll
+  for (int w = 0; w < B / 32; ++w) mdst[w] = mw[w];
+
+  // ---- low part: every channel quantised, the selected ones cleared ----
+  uint32_t dl[B / 8];
+#pragma unroll
+  for (int j = 0; j < B / 8; ++j) {
+    const uint32_t q = quant_lo8(xr + 4 * j, inv_lo);
+    const uint32_t clear = spread_bits_to_nibbles(mw[j / 4] >> (8 * (j % 4)));
+    dl[j] = q & ~clear;
+  }
+  uint4* ddst = reinterpret_cast<uint4*>(d_lo + c.row * (K / 2) + static_cast<int64_t>(c.g) * (B / 2));
+#pragma unroll
+  for (int i = 0; i < B / 32; ++i) ddst[i] = make_uint4(dl[4 * i], dl[4 * i + 1], dl[4 * i + 2], dl[4 * i + 3]);
+}
+
+// Static rule (Algorithm 2): the high channels of a bank are the set bits of a channel mask shared by
+// all tokens.  kt = bits per bank (validated by the caller of the library when the mask is prepacked).
+template <int B, int MAXT>
+__global__ __launch_bounds__(MAXT) void encode_static_kernel(const uint16_t* __restrict__ x, int64_t ldx, int M, int K,
+                                                             int G, int R, int kt, const uint32_t* __restrict__ cmask,
+                                                             uint8_t* __restrict__ d_lo, int8_t* __restrict__ hi_val,
+                                                             float* __restrict__ s_lo, float* __restrict__ s_hi) {
+  __shared__ uint32_t amax_sh[64];
+  __shared__ int8_t stage[MAXT * 32];  // per lane: up to 32 high codes in channel order
+  if (threadIdx.x < 64) amax_sh[threadIdx.x] = 0;
+  __syncthreads();
+  const BankCoord c = bank_coord(G, R, M);
+  uint32_t xr[B / 2];
+  uint32_t mw[B / 32];
+  if (c.active) {
+    const uint4* src = reinterpret_cast<const uint4*>(x + c.row * ldx + static_cast<int64_t>(c.g) * B);
+#pragma unroll
+    for (int i = 0; i < B / 8; ++i) {
+      const uint4 v = src[i];
+      xr[4 * i + 0] = v.x;
+      xr[4 * i + 1] = v.y;
+      xr[4 * i + 2] = v.z;
+      xr[4 * i + 3] = v.w;
+    }
+#pragma unroll
+    for (int w = 0; w < B / 32; ++w) mw[w] = cmask[c.g * (B / 32) + w];
+    uint32_t bank_hi = 0, bank_lo = 0;
+#pragma unroll
+    for (int i = 0; i < B; ++i) {
+      const uint32_t w = xr[i / 2];
+      const uint32_t mag = (i & 1) ? ((w >> 16) & 0x7FFFu) : (w & 0x7FFFu);
+      const bool hi = (mw[i / 32] >> (i % 32)) & 1u;
+      bank_hi = umax(bank_hi, hi ? mag : 0u);
+      bank_lo = umax(bank_lo, hi ? 0u : mag);
+    }
+    atomicMax(&amax_sh[2 * c.r_local], bank_hi);
+    atomicMax(&amax_sh[2 * c.r_local + 1], bank_lo);
+  }
+  __syncthreads();
+  if (!c.active) return;
+
+  const uint32_t ah = amax_sh[2 * c.r_local], al = amax_sh[2 * c.r_local + 1];
+  const float amax_hi = __uint_as_float(ah << 16), amax_lo = __uint_as_float(al << 16);
+  const float inv_hi = ah ? 127.0f / amax_hi : 0.0f;
+  const float inv_lo = al ? 7.0f / amax_lo : 0.0f;
+  if (c.g == 0) {
+    s_hi[c.row] = ah ? amax_hi / 127.0f : 1.0f;
+    s_lo[c.row] = al ? amax_lo / 7.0f : 1.0f;
+  }
+
+  int8_t* my = stage + threadIdx.x * 32;
+  int cnt = 0;
+#pragma unroll
+  for (int i = 0; i < B; ++i) {
+    const bool hi = (mw[i / 32] >> (i % 32)) & 1u;
+    if (hi && cnt < 32) {
+      const uint32_t w = xr[i / 2];
+      const float xf = __uint_as_float((i & 1) ? (w & 0xFFFF0000u) : (w << 16));
+      const float r = __fadd_rn(__fmul_rn(xf, inv_hi), kRoundMagic);
+      my[cnt] = static_cast<int8_t>(__float_as_uint(r) & 0xFFu);
+      ++cnt;
+    }
+  }
+  int8_t* hdst = hi_val + (c.row * G + c.g) * kt;
+  for (int t = 0; t < kt; ++t) hdst[t] = my[t];
+
+  uint32_t dl[B / 8];
+#pragma unroll
+  for (int j = 0; j < B / 8; ++j) {
+    const uint32_t q = quant_lo8(xr + 4 * j, inv_lo);
+    const uint32_t clear = spread_bits_to_nibbles(mw[j / 4] >> (8 * (j % 4)));
+    dl[j] = q & ~clear;
+  }
+  uint4* ddst = reinterpret_cast<uint4*>(d_lo + c.row * (K / 2) + static_cast<int64_t>(c.g) * (B / 2));
+#pragma unroll
+  for (int i = 0; i < B / 32; ++i) ddst[i] = make_uint4(dl[4 * i], dl[4 * i + 1], dl[4 * i + 2], dl[4 * i + 3]);
+}
+
+// (hi_val, mask) -> zero-padded INT8 image of the high part.  Inside every group of 32 channels the
+// bytes are stored even channels first, then odd channels: the order in which the GEMM kernel's
+// nibble unpack delivers a weight row.
+__global__ __launch_bounds__(256) void expand_hi_kernel(const int8_t* __restrict__ hi_val,
+                                                        const uint32_t* __restrict__ mask, int64_t total, int K,
+                                                        int B, int KT, int8_t* __restrict__ out) {
+  __shared__ uint4 stage[256 * 2];
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int wpr = K / 32;
+  const int64_t row = idx / wpr;
+  const int wg = static_cast<int>(idx - row * wpr);
+  const int wpb = B / 32;
+  const int bank = wg / wpb;
+  const uint32_t* mrow = mask + row * wpr;
+  int rank = 0;
+  for (int w = bank * wpb; w < wg; ++w) rank += __popc(mrow[w]);
+  uint32_t word = mrow[wg];
+  const int8_t* src = hi_val + (row * (K / B) + bank) * KT + rank;
+  uint4* my = stage + threadIdx.x * 2;
+  my[0] = make_uint4(0, 0, 0, 0);
+  my[1] = make_uint4(0, 0, 0, 0);
+  int8_t* myb = reinterpret_cast<int8_t*>(my);
+  int left = KT - rank;  // never read past the bank's codes, whatever the mask holds
+  while (word && left > 0) {
+    const int e = __ffs(static_cast<int>(word)) - 1;
+    word &= word - 1;
+    myb[(e & 1) * 16 + (e >> 1)] = *src++;
+    --left;
+  }
+  uint4* dst = reinterpret_cast<uint4*>(out + row * K + static_cast<int64_t>(wg) * 32);
+  dst[0] = my[0];
+  dst[1] = my[1];
+}
+
+// Static mode: compact copy of the high channels' weight columns.  Output row n holds k_hi_padded
+// codes (zero beyond (K/B)*KT); inside every group of 32 codes byte j carries code j in its low and
+// code j+16 in its high nibble, so that the GEMM kernel's unpack yields codes 0..15 and 16..31 in order.
+__global__ __launch_bounds__(256) void weight_prepack_kernel(int N, int K, int B, int KT, int k_hi_padded,
+                                                             const uint8_t* __restrict__ wq,
+                                                             const uint32_t* __restrict__ mask,
+                                                             uint8_t* __restrict__ out) {
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  const int bytes_per_row = k_hi_padded / 2;
+  if (idx >= static_cast<int64_t>(N) * bytes_per_row) return;
+  const int64_t n = idx / bytes_per_row;
+  const int byte = static_cast<int>(idx - n * bytes_per_row);
+  const int grp = byte / 16, j = byte % 16;
+  const int k_hi = mask ? (K / B) * KT : K;
+  uint32_t res = 0;
+  for (int h = 0; h < 2; ++h) {
+    const int t = grp * 32 + j + 16 * h;  // index into the compact list of high channels
+    uint32_t code = 0;
+    if (!mask) {  // every channel, in order (plain W4A8 reference)
+      code = (wq[n * (K / 2) + (t >> 1)] >> ((t & 1) * 4)) & 0xFu;
+    } else if (t < k_hi) {
+      const int bank = t / KT;
+      int r = t % KT;
+      int ch = -1;
+      for (int i = 0; i < B; ++i) {
+        const int cc = bank * B + i;
+        if ((mask[cc >> 5] >> (cc & 31)) & 1u) {
+          if (r == 0) { ch = cc; break; }
+          --r;
+        }
+      }
+      if (ch >= 0) code = (wq[n * (K / 2) + (ch >> 1)] >> ((ch & 1) * 4)) & 0xFu;
+    }
+    res |= code << (4 * h);
+  }
+  out[idx] = static_cast<uint8_t>(res);
+}
+
+template <int B, int KT>
+int launch_dyn(const sq_params& p, const uint16_t* x, int64_t ldx, const sq_act& o, hipStream_t st) {
+  const int G = p.K / B;
+  int R = 256 / G;
+  if (R < 1) R = 1;
+  if (R > 32) R = 32;
+  const int threads = ((R * G + 63) / 64) * 64;
+  const int blocks = (p.M + R - 1) / R;
+  if (threads <= 256) {
+    hipLaunchKernelGGL((encode_dynamic_kernel<B, KT, 256>), dim3(blocks), dim3(threads), 0, st, x, ldx, p.M, p.K, G, R,
+                       o.d_lo, o.hi_val, o.mask, o.scale_lo, o.scale_hi);
+  } else {
+    hipLaunchKernelGGL((encode_dynamic_kernel<B, KT, 512>), dim3(blocks), dim3(threads), 0, st, x, ldx, p.M, p.K, G, R,
+                       o.d_lo, o.hi_val, o.mask, o.scale_lo, o.scale_hi);
+  }
+  return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+template <int B>
+int launch_stat(const sq_params& p, const uint16_t* x, int64_t ldx, const uint32_t* mask, const sq_act& o,
+                hipStream_t st) {
+  const int G = p.K / B;
+  int R = 256 / G;
+  if (R < 1) R = 1;
+  if (R > 32) R = 32;
+  const int threads = ((R * G + 63) / 64) * 64;
+  const int blocks = (p.M + R - 1) / R;
+  if (threads <= 256) {
+    hipLaunchKernelGGL((encode_static_kernel<B, 256>), dim3(blocks), dim3(threads), 0, st, x, ldx, p.M, p.K, G, R,
+                       p.topk, mask, o.d_lo, o.hi_val, o.scale_lo, o.scale_hi);
+  } else {
+    hipLaunchKernelGGL((encode_static_kernel<B, 512>), dim3(blocks), dim3(threads), 0, st, x, ldx, p.M, p.K, G, R,
+                       p.topk, mask, o.d_lo, o.hi_val, o.scale_lo, o.scale_hi);
+  }
+  return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+}  // namespace
+
+int launch_encode_dynamic(const sq_params& p, const uint16_t* x, int64_t ldx, const sq_act& out, hipStream_t st) {
+  // K / bank <= 512 is checked by the caller.
+#define SQ_CASE(B, KT) \
+  if (p.bank == B && p.topk == KT) return launch_dyn<B, KT>(p, x, ldx, out, st);
+  SQ_CASE(32, 2) SQ_CASE(32, 4) SQ_CASE(32, 8) SQ_CASE(32, 16)
+  SQ_CASE(64, 4) SQ_CASE(64, 8) SQ_CASE(64, 16) SQ_CASE(64, 32)
+  SQ_CASE(128, 8) SQ_CASE(128, 16) SQ_CASE(128, 32)
+#undef SQ_CASE
+  return SQ_ERR_UNSUPPORTED;
+}
+
+int launch_encode_static(const sq_params& p, const uint16_t* x, int64_t ldx, const uint32_t* mask, const sq_act& out,
+                         hipStream_t st) {
+  if (p.bank == 32) return launch_stat<32>(p, x, ldx, mask, out, st);
+  if (p.bank == 64) return launch_stat<64>(p, x, ldx, mask, out, st);
+  if (p.bank == 128) return launch_stat<128>(p, x, ldx, mask, out, st);
+  return SQ_ERR_UNSUPPORTED;
+}
+
+int launch_expand_hi(const sq_params& p, const sq_act& a, int8_t* s_hi_dense, hipStream_t st) {
+  const int64_t total = static_cast<int64_t>(p.M) * (p.K / 32);
+  const int64_t blocks = (total + 255) / 256;
+  hipLaunchKernelGGL(expand_hi_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, a.hi_val, a.mask, total,
+                     p.K, p.bank, p.topk, s_hi_dense);
+  return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+int launch_weight_prepack(int N, int K, int bank, int topk, int k_hi_padded, const uint8_t* wq, const uint32_t* mask,
+                          uint8_t* out, hipStream_t st) {
+  const int64_t total = static_cast<int64_t>(N) * (k_hi_padded / 2);
+  const int64_t blocks = (total + 255) / 256;
+  hipLaunchKernelGGL(weight_prepack_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, N, K, bank, topk,
+                     k_hi_padded, wq, mask, out);
+  return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+}  // namespace sq

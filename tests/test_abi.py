@@ -1,0 +1,128 @@
+"""Host-side checks of the C ABI: the library loads, exports what include/sq.h declares, and
+turns every kind of bad argument into an error code before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2512_05409_amd as sq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(sq.LIB_PATH):
+        from paper_2512_05409_amd import build
+        build.build()
+    return sq.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_functions()
+    assert set(names) == set(sq.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings(L):
+    assert sq.status_string(0) == "SQ_OK"
+    for code in range(-7, 0):
+        assert sq.status_string(code).startswith("SQ_ERR_")
+    assert "unknown" in sq.status_string(-99)
+    assert sq.version()
+
+
+def test_sizes(L):
+    p = sq.params(4096, 4096, 22016, 64, 8)
+    nb = sq.sq_act_bytes(p)
+    assert (nb.d_lo, nb.hi_val, nb.mask, nb.scale) == (4096 * 2048, 4096 * 512, 4096 * 512, 4096 * 4)
+    # 0.75 bytes per element + two scales per row (dense low part, compact high part, explicit mask)
+    assert nb.total == 4096 * 4096 * 3 // 4 + 2 * 4096 * 4
+    assert sq.sq_gemm_workspace_bytes(p) == 4096 * 4096
+    assert sq.sq_linear_workspace_bytes(p) >= nb.total + 4096 * 4096
+    assert sq.sq_weight_prepack_bytes(p) == 0
+    ps = sq.params(4096, 11008, 4096, 64, 8, mode=sq.SQ_STATIC)
+    assert sq.sq_weight_prepack_bytes(ps) == 4096 * (11008 // 64 * 8) // 2
+    assert sq.sq_gemm_workspace_bytes(ps) == 16
+    assert sq.sq_act_bytes(ps).mask == 11008 // 32 * 4
+
+
+FAKE = 0x10000  # aligned, never dereferenced: every call below must fail before any launch
+
+
+def _encode(L, p, x=FAKE, ldx=None, mask=None, act=None):
+    a = act if act is not None else sq.sq_act(FAKE, FAKE, FAKE, FAKE, FAKE)
+    return L.sq_encode(ctypes.byref(p), x, p.K if ldx is None else ldx, mask, ctypes.byref(a), None)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(M=0), -2), (dict(K=0), -2), (dict(N=-1), -2),
+    (dict(K=4096 + 32), -2),            # K % 64
+    (dict(K=64 * 3, bank=128), -2),     # K % bank
+    (dict(K=262144), -2),               # K too large
+    (dict(K=32768, bank=32), -2),       # more than 512 banks per row
+    (dict(bank=48), -3), (dict(bank=256), -3),
+    (dict(topk=0), -3), (dict(topk=3), -3), (dict(topk=64, bank=128), -3), (dict(topk=2, bank=64), -3),
+    (dict(mode=2), -3), (dict(out_dtype=5), -3),
+    (dict(mode=1, K=64 * 5, bank=64, topk=4), -3),   # static: compact high width not a multiple of 32
+])
+def test_bad_params_are_refused(L, kw, code):
+    base = dict(M=16, K=512, N=512, bank=64, topk=8, mode=0, out_dtype=0)
+    base.update(kw)
+    p = sq.params(**base)
+    assert _encode(L, p) == code
+    assert L.sq_act_bytes(ctypes.byref(p), None, None, None, None) == 0
+    w = sq.sq_weight(FAKE, FAKE, FAKE)
+    a = sq.sq_act(FAKE, FAKE, FAKE, FAKE, FAKE)
+    assert L.sq_gemm(ctypes.byref(p), ctypes.byref(a), ctypes.byref(w), FAKE, base["N"], None, None, FAKE, 1 << 40, None) == code
+    assert L.sq_linear(ctypes.byref(p), FAKE, base["K"], None, ctypes.byref(w), FAKE, base["N"], FAKE, 1 << 40, None) == code
+
+
+def test_null_alignment_and_leading_dimension(L):
+    p = sq.params(16, 512, 512, 64, 8, out_dtype=0)
+    assert _encode(L, p, x=None) == -1
+    assert _encode(L, p, act=sq.sq_act(FAKE, None, FAKE, FAKE, FAKE)) == -1
+    assert _encode(L, p, x=FAKE + 2) == -4
+    assert _encode(L, p, act=sq.sq_act(FAKE + 4, FAKE, FAKE, FAKE, FAKE)) == -4
+    assert _encode(L, p, ldx=511) == -2
+    assert _encode(L, p, ldx=516) == -4  # rows would not stay 16-byte aligned
+    ps = sq.params(16, 512, 512, 64, 8, mode=1)
+    assert _encode(L, ps, mask=None) == -3  # static mode needs a mask
+    w = sq.sq_weight(FAKE, FAKE, None)
+    a = sq.sq_act(FAKE, FAKE, FAKE, FAKE, FAKE)
+    args = (ctypes.byref(a), ctypes.byref(w), FAKE, 512, None, None)
+    assert L.sq_gemm(ctypes.byref(p), *args, None, 0, None) == -7
+    assert L.sq_gemm(ctypes.byref(p), *args, FAKE, 16 * 512 - 1, None) == -7
+    assert L.sq_gemm(ctypes.byref(p), ctypes.byref(a), ctypes.byref(w), FAKE, 511, None, None, FAKE, 1 << 30, None) == -2
+    assert L.sq_gemm(ctypes.byref(p), ctypes.byref(a), ctypes.byref(w), None, 512, None, None, FAKE, 1 << 30, None) == -1
+    assert L.sq_gemm(ctypes.byref(ps), ctypes.byref(a), ctypes.byref(w), FAKE, 512, None, None, FAKE, 1 << 30, None) == -1  # static needs prepacked
+    assert L.sq_linear(ctypes.byref(p), FAKE, 512, None, ctypes.byref(w), FAKE, 512, FAKE, 16, None) == -7
+    assert L.sq_linear(ctypes.byref(p), FAKE, 512, None, ctypes.byref(w), FAKE, 512, FAKE + 16, 1 << 30, None) == -4
+    assert L.sq_dense_w4a8_gemm(ctypes.byref(p), FAKE, FAKE, ctypes.byref(w), FAKE, 512, None) == -1  # needs prepacked
+
+
+def test_prepack_checks_the_mask_on_the_host(L):
+    ps = sq.params(16, 512, 512, 64, 8, mode=1)
+    good = np.zeros(512 // 32, np.uint32)
+    good[0::2] = 0xFF  # 8 bits in every bank of 64
+    bad = good.copy()
+    bad[2] = 0x7F
+    assert L.sq_weight_prepack(ctypes.byref(ps), FAKE, bad.ctypes.data, FAKE, FAKE, None) == -6
+    pd = sq.params(16, 512, 512, 64, 8, mode=0)
+    assert L.sq_weight_prepack(ctypes.byref(pd), FAKE, good.ctypes.data, FAKE, FAKE, None) == -3
+    assert L.sq_weight_prepack(ctypes.byref(ps), None, good.ctypes.data, FAKE, FAKE, None) == -1
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(ValueError):
+        sq._ptr(torch.zeros(4))

@@ -1,0 +1,107 @@
+"""GPU parity at the benchmark configurations' full sizes, in the launch configuration bench.py times.
+
+The packed encoding is compared for every row; accumulators and outputs for a sample of rows
+spread over M (the oracle's integer product is too slow for all of them), all N columns.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2512_05409_amd as sq
+import workloads
+from gpu_util import assert_encoding_equal, assert_outputs_close, dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def sample_rows(M, n, seed):
+    if M <= n:
+        return np.arange(M)
+    rng = np.random.default_rng(seed)
+    rows = set(rng.choice(M, n - 3, replace=False).tolist()) | {0, M - 1, (M // 128) * 128 - 1 if M >= 128 else 0}
+    return np.array(sorted(rows))
+
+
+def run_config(wl, n_rows, out_dtype=sq.SQ_OUT_BF16, mask=None):
+    M, K, N = wl.M, wl.K, wl.N
+    mode = sq.SQ_STATIC if mask is not None else sq.SQ_DYNAMIC
+    p = sq.params(M, K, N, wl.bank, wl.topk, mode=mode, out_dtype=out_dtype)
+    _say(f"  oracle encode {wl.name} M={M} K={K}")
+    enc = oracle.encode(wl.x_bits, wl.bank, wl.topk, static_mask=mask)
+    xd, wqd, swd = dev(wl.x_bits), dev(wl.wq_packed), dev(wl.w_scale)
+    md = None if mask is None else dev(mask)
+    pre = None
+    if mask is not None:
+        pre = torch.empty(sq.sq_weight_prepack_bytes(p), dtype=torch.uint8, device="cuda")
+        sq.sq_weight_prepack(p, wqd, mask, md, pre)
+    w = sq.weight(wqd, swd, pre)
+    # 1. encode alone: every row
+    act = sq.Act(p, static_mask=md)
+    sq.sq_encode(p, xd, act, static_mask=md)
+    torch.cuda.synchronize()
+    assert_encoding_equal(act, enc)
+    # 2. gemm on that encoding, with the accumulators dumped
+    esz = 4 if out_dtype == sq.SQ_OUT_F32 else 2
+    y = torch.empty(M * N, dtype=torch.float32 if esz == 4 else torch.int16, device="cuda")
+    alo = torch.empty(M * N, dtype=torch.int32, device="cuda")
+    ahi = torch.empty(M * N, dtype=torch.int32, device="cuda")
+    ws = torch.empty(sq.sq_gemm_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    _say("  gpu gemm")
+    sq.sq_gemm(p, act, w, y, ws, acc_lo_dbg=alo, acc_hi_dbg=ahi)
+    torch.cuda.synchronize()
+    rows = sample_rows(M, n_rows, seed=M + N)
+    _say(f"  oracle gemm on {len(rows)} rows")
+    prod = oracle.gemm(enc.rows(rows), wl.wq_packed, wl.w_scale)
+    rd = torch.from_numpy(rows).cuda()
+    assert np.array_equal(alo.view(M, N)[rd].cpu().numpy(), prod.acc_lo), "acc_lo"
+    assert np.array_equal(ahi.view(M, N)[rd].cpu().numpy(), prod.acc_hi), "acc_hi"
+    yh = y.view(M, N)[rd].cpu().numpy()
+    if esz == 4:
+        assert_outputs_close(yh, prod, enc.rows(rows), wl.w_scale)
+    else:
+        assert np.array_equal(yh.view(np.uint16), prod.ybf16), "bf16 outputs"
+    del alo, ahi
+    # 3. the fused entry point the benchmark times must give the same bytes as encode + gemm
+    y2 = torch.empty_like(y)
+    lws = torch.empty(sq.sq_linear_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    _say("  gpu linear")
+    sq.sq_linear(p, xd, w, y2, lws, static_mask=md)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2), "sq_linear != sq_encode + sq_gemm"
+
+
+def test_config1_tiny():
+    _say("config 1")
+    run_config(workloads.make("c1_tiny"), n_rows=16, out_dtype=sq.SQ_OUT_F32)
+    run_config(workloads.make("c1_tiny"), n_rows=16, out_dtype=sq.SQ_OUT_BF16)
+
+
+def test_config2_qkv7b():
+    _say("config 2")
+    run_config(workloads.make("c2_qkv7b"), n_rows=12)
+
+
+@pytest.mark.parametrize("bank,topk", [(64, 8), (32, 2), (32, 8), (64, 4), (64, 16), (128, 8), (128, 32)])
+def test_config3_mlp7b(bank, topk):
+    _say(f"config 3 bank={bank} topk={topk}")
+    # the (b, k) sweep reuses the shape with a reduced N except for the headline setting
+    N = None if (bank, topk) == (64, 8) else 2048
+    run_config(workloads.make("c3_mlp7b", bank=bank, topk=topk, N=N), n_rows=8)
+
+
+def test_config4_down7b_static():
+    _say("config 4")
+    wl = workloads.make("c4_down7b_static")
+    mask, _ = oracle.static_mask(wl.calib_bits, wl.wq_packed, wl.w_scale, wl.bank, wl.topk)
+    run_config(wl, n_rows=8, mask=mask)
+
+
+@pytest.mark.parametrize("M", [1, 8, 64, 8192])
+def test_config5_up70b(M):
+    _say(f"config 5 M={M}")
+    run_config(workloads.make("c5_up70b", M=M), n_rows=6)

@@ -1,0 +1,226 @@
+"""GPU parity: libsq (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Bit-exact: packed encodings (codes, mask, scale bit patterns) and both INT32 accumulators.
+fp32 outputs: relative error <= 1e-6 against the oracle's fp32 evaluation and within three
+roundings of its fp64 evaluation; bf16 outputs: identical bit patterns.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2512_05409_amd as sq
+import workloads
+from workloads import f32_to_bf16_bits, pack_int4
+from gpu_util import Guarded, GuardedAct, assert_encoding_equal, assert_outputs_close, dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def random_case(seed, M, K, N, outliers=6):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, rng.choice(K, outliers, replace=False)] *= rng.uniform(20, 50, outliers).astype(np.float32)
+    # a few rows with heavy ties and a zero row, to exercise the tie-break and the degenerate scales
+    if M > 3:
+        x[1] = rng.choice(np.array([0.0, 0.5, -0.5, 1.0, 2.0, -2.0], np.float32), size=K)
+        x[2] = 0.0
+        x[3] = 1.0
+    w = rng.integers(-8, 8, size=(N, K)).astype(np.int8)
+    sw = rng.uniform(0.005, 0.02, N).astype(np.float32)
+    return f32_to_bf16_bits(x), pack_int4(w), sw
+
+
+def run_encode(bits, bank, topk, static_mask=None, ldx=None):
+    M, K = bits.shape
+    mode = sq.SQ_DYNAMIC if static_mask is None else sq.SQ_STATIC
+    p = sq.params(M, K, 64, bank, topk, mode=mode)
+    if ldx is None:
+        xd = dev(bits)
+    else:
+        padded = np.full((M, ldx), 0x7F80, np.uint16)  # +inf in the padding: must never be read as data
+        padded[:, :K] = bits
+        xd = dev(padded)
+    md = None if static_mask is None else dev(static_mask)
+    act = GuardedAct(p, static_mask=md)
+    sq.sq_encode(p, xd, act, static_mask=md, ldx=ldx)
+    torch.cuda.synchronize()
+    act.check()
+    return p, act
+
+
+@pytest.mark.parametrize("bank,topk", [(64, 8), (32, 2), (32, 4), (32, 8), (32, 16), (64, 4), (64, 16), (64, 32),
+                                       (128, 8), (128, 16), (128, 32)])
+def test_encode_dynamic_bit_exact(bank, topk):
+    _say(f"encode dynamic bank={bank} topk={topk}")
+    bits, _, _ = random_case(100 + bank + topk, M=37, K=1024, N=8)
+    p, act = run_encode(bits, bank, topk)
+    assert_encoding_equal(act, oracle.encode(bits, bank, topk))
+
+
+@pytest.mark.parametrize("M,K,bank,topk", [(1, 64, 64, 8), (3, 128, 128, 8), (5, 8192, 64, 8), (2, 11008, 64, 8),
+                                           (2, 11008, 32, 4), (3, 16384, 32, 8), (130, 512, 64, 8), (9, 4096, 128, 16)])
+def test_encode_dynamic_shapes(M, K, bank, topk):
+    _say(f"encode dynamic shape M={M} K={K} bank={bank} topk={topk}")
+    bits, _, _ = random_case(7 * M + K, M=M, K=K, N=8, outliers=min(6, K // 16))
+    p, act = run_encode(bits, bank, topk)
+    assert_encoding_equal(act, oracle.encode(bits, bank, topk))
+
+
+def test_encode_leading_dimension_and_determinism():
+    _say("encode ldx / determinism")
+    bits, _, _ = random_case(5, M=20, K=512, N=8)
+    p, a1 = run_encode(bits, 64, 8, ldx=512 + 64)
+    enc = oracle.encode(bits, 64, 8)
+    assert_encoding_equal(a1, enc)
+    p, a2 = run_encode(bits, 64, 8)
+    for f in ("d_lo", "hi_val", "mask", "scale_lo", "scale_hi"):
+        assert torch.equal(getattr(a1, f), getattr(a2, f))
+
+
+def make_static_mask(K, bank, topk, seed):
+    rng = np.random.default_rng(seed)
+    mask = np.zeros(K // 32, np.uint32)
+    for g in range(K // bank):
+        for i in rng.choice(bank, topk, replace=False):
+            j = g * bank + int(i)
+            mask[j // 32] |= np.uint32(1 << (j % 32))
+    return mask
+
+
+@pytest.mark.parametrize("K,bank,topk", [(512, 64, 8), (1024, 32, 4), (2048, 128, 16), (11008, 64, 8), (512, 64, 4)])
+def test_encode_static_bit_exact(K, bank, topk):
+    _say(f"encode static K={K} bank={bank} topk={topk}")
+    bits, _, _ = random_case(300 + K + bank, M=21, K=K, N=8)
+    mask = make_static_mask(K, bank, topk, seed=K + topk)
+    p, act = run_encode(bits, bank, topk, static_mask=mask)
+    assert_encoding_equal(act, oracle.encode(bits, bank, topk, static_mask=mask))
+
+
+def run_gemm(p, enc_host, wq, sw, out_dtype, prepacked=None, static_mask=None):
+    """Upload an oracle encoding and run sq_gemm on it; returns (y, acc_lo, acc_hi) host arrays."""
+    M, N = p.M, p.N
+    md = None if static_mask is None else dev(static_mask)
+    act = sq.Act(p, static_mask=md)
+    act.d_lo.copy_(dev(enc_host.d_lo).view(-1))
+    act.hi_val.copy_(dev(enc_host.hi_val).view(-1))
+    if p.mode == sq.SQ_DYNAMIC:
+        act.mask.copy_(dev(enc_host.mask).view(-1))
+    act.scale_lo.copy_(dev(enc_host.s_lo))
+    act.scale_hi.copy_(dev(enc_host.s_hi))
+    wqd, swd = dev(wq), dev(sw)
+    w = sq.weight(wqd, swd, prepacked)
+    esz = 4 if out_dtype == sq.SQ_OUT_F32 else 2
+    y = Guarded(M * N * esz, torch.float32 if esz == 4 else torch.int16)
+    alo = Guarded(M * N * 4, torch.int32)
+    ahi = Guarded(M * N * 4, torch.int32)
+    ws = torch.empty(sq.sq_gemm_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    sq.sq_gemm(p, act, w, y.t, ws, acc_lo_dbg=alo.t, acc_hi_dbg=ahi.t)
+    torch.cuda.synchronize()
+    for g in (y, alo, ahi):
+        g.check()
+    yh = y.host(np.float32 if esz == 4 else np.uint16).reshape(M, N)
+    return yh, alo.host(np.int32).reshape(M, N), ahi.host(np.int32).reshape(M, N)
+
+
+@pytest.mark.parametrize("M,K,N,bank,topk", [(16, 512, 512, 64, 8), (200, 1024, 300, 64, 8), (129, 320, 130, 32, 4),
+                                             (64, 2048, 256, 128, 16), (1, 512, 128, 64, 8), (257, 64, 5, 64, 16)])
+def test_gemm_dynamic_accumulators_and_outputs(M, K, N, bank, topk):
+    _say(f"gemm dynamic M={M} K={K} N={N} bank={bank} topk={topk}")
+    bits, wq, sw = random_case(1000 + M + K + N, M, K, N, outliers=min(6, K // 16))
+    enc = oracle.encode(bits, bank, topk)
+    prod = oracle.gemm(enc, wq, sw)
+    p = sq.params(M, K, N, bank, topk, out_dtype=sq.SQ_OUT_F32)
+    y, alo, ahi = run_gemm(p, enc, wq, sw, sq.SQ_OUT_F32)
+    assert np.array_equal(alo, prod.acc_lo), "acc_lo"
+    assert np.array_equal(ahi, prod.acc_hi), "acc_hi"
+    assert_outputs_close(y, prod, enc, sw)
+    assert np.array_equal(y.view(np.uint32), prod.y32.view(np.uint32)), "fp32 outputs are expected to be bit-identical"
+    p16 = sq.params(M, K, N, bank, topk, out_dtype=sq.SQ_OUT_BF16)
+    y16, _, _ = run_gemm(p16, enc, wq, sw, sq.SQ_OUT_BF16)
+    assert np.array_equal(y16, prod.ybf16)
+
+
+def test_gemm_extreme_codes_do_not_overflow():
+    # every low code +-7, every high code +-127, every weight -8: the largest accumulators K allows
+    _say("gemm extreme codes")
+    M, K, N, bank, topk = 8, 2048, 64, 64, 16
+    x = np.full((M, K), 1.0, np.float32)
+    x[:, ::4] = 64.0  # k/b = 1/4 of the channels are the high ones
+    x[1::2] *= -1
+    bits = f32_to_bf16_bits(x)
+    wq = pack_int4(np.full((N, K), -8, np.int8))
+    sw = np.full(N, 0.01, np.float32)
+    enc = oracle.encode(bits, bank, topk)
+    prod = oracle.gemm(enc, wq, sw)
+    assert abs(int(prod.acc_lo[0, 0])) == 7 * 8 * (K * 3 // 4) and abs(int(prod.acc_hi[0, 0])) == 127 * 8 * (K // 4)
+    p = sq.params(M, K, N, bank, topk, out_dtype=sq.SQ_OUT_F32)
+    y, alo, ahi = run_gemm(p, enc, wq, sw, sq.SQ_OUT_F32)
+    assert np.array_equal(alo, prod.acc_lo) and np.array_equal(ahi, prod.acc_hi)
+
+
+@pytest.mark.parametrize("M,K,N,bank,topk", [(16, 512, 512, 64, 8), (150, 1024, 200, 32, 4), (40, 11008, 64, 64, 8)])
+def test_gemm_static(M, K, N, bank, topk):
+    _say(f"gemm static M={M} K={K} N={N} bank={bank} topk={topk}")
+    bits, wq, sw = random_case(2000 + M + K + N, M, K, N)
+    mask = make_static_mask(K, bank, topk, seed=K + 3)
+    enc = oracle.encode(bits, bank, topk, static_mask=mask)
+    prod = oracle.gemm(enc, wq, sw)
+    p = sq.params(M, K, N, bank, topk, mode=sq.SQ_STATIC, out_dtype=sq.SQ_OUT_F32)
+    pre = torch.empty(sq.sq_weight_prepack_bytes(p), dtype=torch.uint8, device="cuda")
+    wqd, md = dev(wq), dev(mask)
+    sq.sq_weight_prepack(p, wqd, mask, md, pre)
+    y, alo, ahi = run_gemm(p, enc, wq, sw, sq.SQ_OUT_F32, prepacked=pre, static_mask=mask)
+    assert np.array_equal(alo, prod.acc_lo), "acc_lo"
+    assert np.array_equal(ahi, prod.acc_hi), "acc_hi"
+    assert_outputs_close(y, prod, enc, sw)
+
+
+@pytest.mark.parametrize("mode", ["dynamic", "static"])
+def test_linear_end_to_end(mode):
+    _say(f"linear {mode}")
+    M, K, N, bank, topk = 70, 1024, 192, 64, 8
+    bits, wq, sw = random_case(3000, M, K, N)
+    mask = make_static_mask(K, bank, topk, seed=9) if mode == "static" else None
+    enc = oracle.encode(bits, bank, topk, static_mask=mask)
+    prod = oracle.gemm(enc, wq, sw)
+    p = sq.params(M, K, N, bank, topk, mode=sq.SQ_STATIC if mask is not None else sq.SQ_DYNAMIC, out_dtype=sq.SQ_OUT_BF16)
+    xd, wqd, swd = dev(bits), dev(wq), dev(sw)
+    md = None if mask is None else dev(mask)
+    pre = None
+    if mask is not None:
+        pre = torch.empty(sq.sq_weight_prepack_bytes(p), dtype=torch.uint8, device="cuda")
+        sq.sq_weight_prepack(p, wqd, mask, md, pre)
+    w = sq.weight(wqd, swd, pre)
+    y = Guarded(M * N * 2, torch.int16)
+    ws = Guarded(sq.sq_linear_workspace_bytes(p), torch.uint8)
+    sq.sq_linear(p, xd, w, y.t, ws.t, static_mask=md)
+    torch.cuda.synchronize()
+    y.check()
+    ws.check()
+    assert np.array_equal(y.host(np.uint16).reshape(M, N), prod.ybf16)
+
+
+def test_dense_w4a8_reference_kernel():
+    _say("dense w4a8")
+    rng = np.random.default_rng(77)
+    M, K, N = 100, 768, 140
+    a = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    sa = rng.uniform(0.01, 0.1, M).astype(np.float32)
+    w = rng.integers(-8, 8, size=(N, K)).astype(np.int8)
+    sw = rng.uniform(0.005, 0.02, N).astype(np.float32)
+    p = sq.params(M, K, N, out_dtype=sq.SQ_OUT_F32)
+    wqd, swd = dev(pack_int4(w)), dev(sw)
+    pre = torch.empty(N * K // 2, dtype=torch.uint8, device="cuda")
+    sq.sq_dense_w4a8_prepack(p, wqd, pre)
+    y = Guarded(M * N * 4, torch.float32)
+    sq.sq_dense_w4a8_gemm(p, dev(a), dev(sa), sq.weight(wqd, swd, pre), y.t)
+    torch.cuda.synchronize()
+    y.check()
+    acc = a.astype(np.int64) @ w.astype(np.int64).T
+    want = (acc.astype(np.float32) * sa[:, None]).astype(np.float32) * sw[None, :]
+    assert np.array_equal(y.host(np.float32).reshape(M, N), want.astype(np.float32))
