@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of the SQ-format linear layer (sq_encode + sq_gemm) on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch: bf16 activations -> SQ-format ->
+both integer products -> dequantised bf16 output.  The step is issued as sq_encode followed by
+sq_gemm (exactly what sq_linear enqueues) so that HIP events between the two launches give the
+duration of each kernel inside the timed region.  Inputs are synthetic, seeded, already in HBM.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_PEAK_TOPS = 5000.0  # MI355X dense INT8 matrix peak (vendor figure, no sparsity), TOP/s
+HBM_PEAK_GBS = 8000.0    # MI355X HBM3E peak, GB/s
+
+WORKLOADS = {
+    "c2": ("c2_qkv7b", {}),
+    "c3": ("c3_mlp7b", {}),
+    "c4": ("c4_down7b_static", {}),
+    "c5": ("c5_up70b", {}),
+}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c3", choices=sorted(WORKLOADS), help="benchmark configuration (default: the 7B MLP shape)")
+    ap.add_argument("--M", type=int, default=None)
+    ap.add_argument("--bank", type=int, default=None)
+    ap.add_argument("--topk", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the CPU-oracle sample (0: sized for about 15 s)")
+    return ap.parse_args()
+
+
+def dev(a):
+    import torch
+
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    elif a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(a).cuda()
+
+
+def cpu_baseline(wl, mask, rows_req):
+    """The oracle as it stands, timed on the host cores, on a bounded row sample of the same workload."""
+    import oracle
+
+    oracle.build()
+    cores = oracle.num_threads()
+    # size the sample from a short probe so that the whole leg stays near 15 s
+    probe_rows = np.linspace(0, wl.M - 1, num=min(wl.M, 2 * cores), dtype=np.int64)
+    t0 = time.perf_counter()
+    enc = oracle.encode(wl.x_bits[probe_rows], wl.bank, wl.topk, static_mask=mask)
+    oracle.gemm(enc, wl.wq_packed, wl.w_scale, want_y64=False)
+    t_probe = time.perf_counter() - t0
+    if rows_req > 0:
+        n = min(wl.M, rows_req)
+    else:
+        n = int(min(wl.M, max(len(probe_rows), len(probe_rows) * 15.0 / max(t_probe, 1e-3))))
+        n = max(cores, (n // cores) * cores)
+    rows = np.linspace(0, wl.M - 1, num=n, dtype=np.int64)
+    xs = np.ascontiguousarray(wl.x_bits[rows])
+    t0 = time.perf_counter()
+    enc = oracle.encode(xs, wl.bank, wl.topk, static_mask=mask)
+    t_enc = time.perf_counter() - t0
+    oracle.gemm(enc, wl.wq_packed, wl.w_scale, want_y64=False)
+    t_all = time.perf_counter() - t0
+    tops = 2.0 * n * wl.N * wl.K / t_all / 1e12
+    return {
+        "value": tops, "unit": "TOPS", "cores": cores, "kind": "oracle",
+        "sample": f"{n} of {wl.M} token rows (evenly spaced), all {wl.N} output channels: encode + both products + epilogue",
+        "seconds": round(t_all, 3), "encode_seconds": round(t_enc, 3),
+        "extrapolated_full_seconds": round(t_all * wl.M / n, 1),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding or collectives are part of it); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2512_05409_amd as sq
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    sq.lib()
+
+    name, kw = WORKLOADS[args.workload]
+    kw = dict(kw)
+    if args.M is not None:
+        kw["M"] = args.M
+    if args.bank is not None:
+        kw["bank"] = args.bank
+    if args.topk is not None:
+        kw["topk"] = args.topk
+    wl = workloads.make(name, **kw)
+    M, K, N, b, k = wl.M, wl.K, wl.N, wl.bank, wl.topk
+    static = wl.mode == "static"
+
+    mask = None
+    if static:
+        # The channel mask is an input of the layer (it comes from the PTQ pipeline).  Timing does not
+        # depend on which channels it names, so the benchmark draws one (outlier channels + random fill).
+        mask = workloads.drawn_static_mask(wl)
+
+    p = sq.params(M, K, N, b, k, mode=sq.SQ_STATIC if static else sq.SQ_DYNAMIC, out_dtype=sq.SQ_OUT_BF16)
+    wqd, swd = dev(wl.wq_packed), dev(wl.w_scale)
+    md = dev(mask) if static else None
+    pre = None
+    if static:
+        pre = torch.empty(sq.sq_weight_prepack_bytes(p), dtype=torch.uint8, device="cuda")
+        sq.sq_weight_prepack(p, wqd, mask, md, pre)
+    w = sq.weight(wqd, swd, pre)
+
+    # Rotating buffers: X copies whose total exceeds the 256 MB Infinity Cache, so the encoder reads HBM.
+    x_bytes = M * K * 2
+    n_x = max(2, min(16, -(-300_000_000 // x_bytes)))
+    x0 = dev(wl.x_bits)
+    xs = [x0] + [x0.clone() for _ in range(n_x - 1)]
+    n_y = 2
+    ys = [torch.empty(M * N, dtype=torch.int16, device="cuda") for _ in range(n_y)]
+    acts = [sq.Act(p, static_mask=md, with_hi_dense=True) for _ in range(2)]
+
+    def step(i, ev=None):
+        a = acts[i % 2]
+        if ev is not None:
+            ev[0].record()
+        sq.sq_encode(p, xs[i % n_x], a, static_mask=md)
+        if ev is not None:
+            ev[1].record()
+        sq.sq_gemm(p, a, w, ys[i % n_y], None)
+        if ev is not None:
+            ev[2].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    enc_ms = np.array([e[0].elapsed_time(e[1]) for e in events])
+    gemm_ms = np.array([e[1].elapsed_time(e[2]) for e in events])
+    ms_per_step = wall * 1e3 / args.steps
+    ops_eff = 2.0 * M * N * K
+    eff_tops = ops_eff / (ms_per_step * 1e-3) / 1e12
+
+    # Algorithmic work of the dominant kernel (the GEMM): both products the layer is defined with.
+    alg_ops = 2.0 * M * N * K * (1.0 + k / b)
+    issued_ops = 2.0 * M * N * K * (1.0 + (k / b if static else 1.0))  # dynamic: the high pass is zero-padded to dense
+    gemm_s = float(gemm_ms.mean()) * 1e-3
+    enc_s = float(enc_ms.mean()) * 1e-3
+    enc_bytes = M * K * 2 + M * K // 2 + M * (K // b) * k + (0 if static else M * K // 8) + 8 * M
+    enc_bytes_written_extra = 0 if static else M * K  # the matrix-core-ready image of the high part
+
+    out = {
+        "metric": "SQ-format linear effective TOPS (encode+GEMM) and % of INT8 MFMA peak, 1 GPU",
+        "value": eff_tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"{name}: X bf16 [{M},{K}] -> SQ-format bank={b} topk={k} {wl.mode}; "
+                               f"W INT4 [{N},{K}] per-row scales; Y bf16 [{M},{N}]",
+                   "M": M, "K": K, "N": N, "bank": b, "topk": k, "mode": wl.mode, "out": "bf16",
+                   "x_buffers_rotated": n_x},
+        "pct_int8_peak_effective": 100.0 * eff_tops / INT8_PEAK_TOPS,
+        "roofline": {"kernel": "sq_gemm", "bound": "mfma", "achieved": alg_ops / gemm_s / 1e12, "peak": INT8_PEAK_TOPS,
+                     "unit": "TOP/s", "frac": alg_ops / gemm_s / 1e12 / INT8_PEAK_TOPS, "traffic": None,
+                     "ms": gemm_s * 1e3, "ms_min": float(gemm_ms.min()),
+                     "algorithmic_ops": alg_ops, "issued_mfma_ops": issued_ops,
+                     "issued_frac": issued_ops / gemm_s / 1e12 / INT8_PEAK_TOPS,
+                     "effective_tops_2MNK": ops_eff / gemm_s / 1e12},
+        "encode": {"kernel": "sq_encode", "bound": "hbm", "achieved": enc_bytes / enc_s / 1e9, "peak": HBM_PEAK_GBS,
+                   "unit": "GB/s", "frac": enc_bytes / enc_s / 1e9 / HBM_PEAK_GBS, "ms": enc_s * 1e3,
+                   "ms_min": float(enc_ms.min()), "algorithmic_bytes": enc_bytes,
+                   "extra_bytes_written_hi_dense": enc_bytes_written_extra,
+                   "achieved_incl_hi_dense": (enc_bytes + enc_bytes_written_extra) / enc_s / 1e9},
+    }
+
+    if not args.no_dense_baseline:
+        # Plain per-token W4A8 of the same shape on the same matrix-core kernel (what W4A8 falls back to).
+        pd = sq.params(M, K, N, out_dtype=sq.SQ_OUT_BF16)
+        a8 = torch.randint(-127, 128, (M, K), dtype=torch.int8, device="cuda")
+        sa = torch.rand(M, dtype=torch.float32, device="cuda") * 0.1 + 0.01
+        pre8 = torch.empty(N * K // 2, dtype=torch.uint8, device="cuda")
+        sq.sq_dense_w4a8_prepack(pd, wqd, pre8)
+        w8 = sq.weight(wqd, swd, pre8)
+        for i in range(3):
+            sq.sq_dense_w4a8_gemm(pd, a8, sa, w8, ys[i % n_y])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(5, args.steps // 2)
+        e0.record()
+        for i in range(reps):
+            sq.sq_dense_w4a8_gemm(pd, a8, sa, w8, ys[i % n_y])
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        out["dense_w4a8_baseline"] = {"ms": ms, "tops": ops_eff / (ms * 1e-3) / 1e12,
+                                      "frac_int8_peak": ops_eff / (ms * 1e-3) / 1e12 / INT8_PEAK_TOPS,
+                                      "note": "per-token INT8 activations x INT4 weights, same kernel, no SQ split"}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, mask, args.cpu_rows)
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

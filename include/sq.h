@@ -70,6 +70,11 @@ typedef struct {
                        bit (j % 32) of word j/32 set <=> channel j is high precision */
   float *scale_lo;  /* [M] per-token scale of the low part  (largest low magnitude / 7) */
   float *scale_hi;  /* [M] per-token scale of the high part (largest high magnitude / 127) */
+  int8_t *hi_dense; /* optional (may be NULL), dynamic mode only: [M, K] matrix-core-ready image of the high part,
+                       a pure function of (hi_val, mask): the INT8 codes at their channels, 0 elsewhere, the 32
+                       channels of every group stored even channels first, then odd channels.  sq_encode writes
+                       it when the pointer is set; sq_gemm uses it when set and otherwise builds it in its
+                       workspace.  Not part of the format: a cache that saves sq_gemm one pass. */
 } sq_act;
 
 /* Plain INT4 weights with one fp32 scale per output channel. */
@@ -83,11 +88,11 @@ typedef struct {
  * Returns the total; any out pointer may be NULL.  Returns 0 if the parameters are invalid. */
 size_t sq_act_bytes(const sq_params *p, size_t *d_lo, size_t *hi_val, size_t *mask, size_t *scale);
 
-/* Bytes of device workspace sq_gemm needs (dynamic: the zero-padded INT8 image of the high
- * part, M*K bytes; static: 0 -> returns 16 so that a valid pointer can always be passed). */
+/* Bytes of device workspace sq_gemm needs when a->hi_dense is NULL (dynamic: the image of the
+ * high part, M*K bytes; static: none -> returns 16 so that a valid pointer can always be passed). */
 size_t sq_gemm_workspace_bytes(const sq_params *p);
 
-/* Bytes of device workspace sq_linear needs: an sq_act plus sq_gemm's workspace. */
+/* Bytes of device workspace sq_linear needs: an sq_act including hi_dense. */
 size_t sq_linear_workspace_bytes(const sq_params *p);
 
 /* Bytes of the prepacked weight image for the static mode (0 in dynamic mode). */
@@ -122,7 +127,8 @@ int sq_encode(const sq_params *p, const uint16_t *x_bf16, int64_t ldx, const uin
  *   y           device [M, ldy] fp32 or bf16 (p->out_dtype), ldy >= N (elements)
  *   acc_lo_dbg  optional device [M, N] int32: the exact low-part accumulators
  *   acc_hi_dbg  optional device [M, N] int32: the exact high-part accumulators
- *   workspace   device, sq_gemm_workspace_bytes(p) bytes, contents destroyed
+ *   workspace   device, sq_gemm_workspace_bytes(p) bytes, contents destroyed; may be NULL (size 0) when
+ *               a->hi_dense is set or in static mode
  */
 int sq_gemm(const sq_params *p, const sq_act *a, const sq_weight *w, void *y, int64_t ldy,
             int32_t *acc_lo_dbg, int32_t *acc_hi_dbg, void *workspace, size_t workspace_bytes, void *stream);

@@ -38,7 +38,7 @@ class sq_params(ctypes.Structure):
 
 class sq_act(ctypes.Structure):
     _fields_ = [("d_lo", ctypes.c_void_p), ("hi_val", ctypes.c_void_p), ("mask", ctypes.c_void_p),
-                ("scale_lo", ctypes.c_void_p), ("scale_hi", ctypes.c_void_p)]
+                ("scale_lo", ctypes.c_void_p), ("scale_hi", ctypes.c_void_p), ("hi_dense", ctypes.c_void_p)]
 
 
 class sq_weight(ctypes.Structure):
@@ -145,11 +145,14 @@ def sq_weight_prepack_bytes(p: sq_params) -> int:
 class Act:
     """Device buffers of one SQ-format activation matrix (torch tensors, caller-visible)."""
 
-    def __init__(self, p: sq_params, device="cuda", static_mask=None):
+    def __init__(self, p: sq_params, device="cuda", static_mask=None, with_hi_dense=False):
         import torch
 
         nb = sq_act_bytes(p)
         self.p = p
+        self.hi_dense = None
+        if with_hi_dense and p.mode == SQ_DYNAMIC:
+            self.hi_dense = torch.empty(p.M * p.K, dtype=torch.int8, device=device)
         self.d_lo = torch.empty(nb.d_lo, dtype=torch.uint8, device=device)
         self.hi_val = torch.empty(nb.hi_val, dtype=torch.int8, device=device)
         if p.mode == SQ_DYNAMIC:
@@ -161,7 +164,8 @@ class Act:
         self.scale_hi = torch.empty(p.M, dtype=torch.float32, device=device)
 
     def c(self) -> sq_act:
-        return sq_act(_ptr(self.d_lo), _ptr(self.hi_val), _ptr(self.mask), _ptr(self.scale_lo), _ptr(self.scale_hi))
+        return sq_act(_ptr(self.d_lo), _ptr(self.hi_val), _ptr(self.mask), _ptr(self.scale_lo), _ptr(self.scale_hi),
+                      _ptr(getattr(self, "hi_dense", None)))
 
 
 def weight(wq, scale, prepacked=None) -> sq_weight:
@@ -188,7 +192,8 @@ def sq_gemm(p: sq_params, a: Act, w: sq_weight, y, workspace, acc_lo_dbg=None, a
     ac = a.c()
     _check(lib().sq_gemm(ctypes.byref(p), ctypes.byref(ac), ctypes.byref(w), _ptr(y), p.N if ldy is None else ldy,
                          _ptr(acc_lo_dbg), _ptr(acc_hi_dbg), _ptr(workspace),
-                         workspace.numel() * workspace.element_size(), _stream(stream)), "sq_gemm")
+                         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)),
+           "sq_gemm")
 
 
 def sq_linear(p: sq_params, x_bf16, w: sq_weight, y, workspace, static_mask=None, ldx: Optional[int] = None,

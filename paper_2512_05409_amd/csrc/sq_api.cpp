@@ -43,7 +43,7 @@ ActLayout act_layout(const sq_params* p) {
 int check_act(const sq_params* p, const sq_act* a) {
   if (!a || !a->d_lo || !a->hi_val || !a->mask || !a->scale_lo || !a->scale_hi) return SQ_ERR_NULL;
   if (!aligned16(a->d_lo) || !aligned16(a->hi_val) || !aligned16(a->mask) || !aligned16(a->scale_lo) ||
-      !aligned16(a->scale_hi))
+      !aligned16(a->scale_hi) || !aligned16(a->hi_dense))
     return SQ_ERR_ALIGN;
   (void)p;
   return SQ_OK;
@@ -87,8 +87,8 @@ size_t sq_linear_workspace_bytes(const sq_params* p) {
   if (check_params(p) != SQ_OK) return 0;
   const ActLayout l = act_layout(p);
   size_t t = align_up(l.d_lo, 256) + align_up(l.hi_val, 256) + 2 * align_up(l.scale, 256);
-  if (p->mode == SQ_DYNAMIC) t += align_up(l.mask, 256);
-  return t + sq_gemm_workspace_bytes(p);
+  if (p->mode == SQ_DYNAMIC) t += align_up(l.mask, 256) + align_up(static_cast<size_t>(p->M) * p->K, 256);
+  return t;
 }
 
 size_t sq_weight_prepack_bytes(const sq_params* p) {
@@ -140,8 +140,9 @@ int sq_gemm(const sq_params* p, const sq_act* a, const sq_weight* w, void* y, in
   if ((rc = check_act(p, a)) != SQ_OK) return rc;
   if ((rc = check_weight(p, w)) != SQ_OK) return rc;
   if ((rc = check_y(p, y, ldy)) != SQ_OK) return rc;
-  if (!workspace || workspace_bytes < sq_gemm_workspace_bytes(p)) return SQ_ERR_WORKSPACE;
-  if (!aligned16(workspace)) return SQ_ERR_ALIGN;
+  const bool need_ws = p->mode == SQ_DYNAMIC && !a->hi_dense;
+  if (need_ws && (!workspace || workspace_bytes < sq_gemm_workspace_bytes(p))) return SQ_ERR_WORKSPACE;
+  if (need_ws && !aligned16(workspace)) return SQ_ERR_ALIGN;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   sq::GemmArgs g;
@@ -160,9 +161,13 @@ int sq_gemm(const sq_params* p, const sq_act* a, const sq_weight* w, void* y, in
   g.acc_lo_dbg = acc_lo_dbg;
   g.acc_hi_dbg = acc_hi_dbg;
   if (p->mode == SQ_DYNAMIC) {
-    rc = sq::launch_expand_hi(*p, *a, static_cast<int8_t*>(workspace), st);
-    if (rc != SQ_OK) return rc;
-    g.a_hi_dense = static_cast<const int8_t*>(workspace);
+    if (a->hi_dense) {
+      g.a_hi_dense = a->hi_dense;
+    } else {
+      rc = sq::launch_expand_hi(*p, *a, static_cast<int8_t*>(workspace), st);
+      if (rc != SQ_OK) return rc;
+      g.a_hi_dense = static_cast<const int8_t*>(workspace);
+    }
   } else {
     g.K_hi = k_hi_of(p);
     g.a_hi_compact = a->hi_val;
@@ -193,16 +198,18 @@ int sq_linear(const sq_params* p, const uint16_t* x_bf16, int64_t ldx, const uin
   ws += align_up(l.scale, 256);
   a.scale_hi = reinterpret_cast<float*>(ws);
   ws += align_up(l.scale, 256);
+  a.hi_dense = nullptr;
   if (p->mode == SQ_DYNAMIC) {
     a.mask = reinterpret_cast<uint32_t*>(ws);
     ws += align_up(l.mask, 256);
+    a.hi_dense = reinterpret_cast<int8_t*>(ws);
+    ws += align_up(static_cast<size_t>(p->M) * p->K, 256);
   } else {
     a.mask = const_cast<uint32_t*>(static_mask);
   }
   rc = sq_encode(p, x_bf16, ldx, static_mask, &a, stream);
   if (rc != SQ_OK) return rc;
-  const size_t used = static_cast<size_t>(ws - static_cast<char*>(workspace));
-  return sq_gemm(p, &a, w, y, ldy, nullptr, nullptr, ws, workspace_bytes - used, stream);
+  return sq_gemm(p, &a, w, y, ldy, nullptr, nullptr, nullptr, 0, stream);
 }
 
 int sq_dense_w4a8_prepack(const sq_params* p, const uint8_t* wq, void* out, void* stream) {

@@ -126,7 +126,9 @@ template <int B, int KT, int MAXT>
 __global__ __launch_bounds__(MAXT) void encode_dynamic_kernel(const uint16_t* __restrict__ x, int64_t ldx, int M, int K,
                                                               int G, int R, uint8_t* __restrict__ d_lo,
                                                               int8_t* __restrict__ hi_val, uint32_t* __restrict__ mask,
-                                                              float* __restrict__ s_lo, float* __restrict__ s_hi) {
+                                                              float* __restrict__ s_lo, float* __restrict__ s_hi,
+                                                              int8_t* __restrict__ hi_dense) {
+  extern __shared__ __attribute__((aligned(16))) char dense_stage[];  // blockDim * B bytes when hi_dense is set
   static_assert(B % 32 == 0 && KT >= 1 && KT <= 32 && (KT & (KT - 1)) == 0 && B % KT == 0 && B / KT >= 2, "shape");
   __shared__ uint32_t amax_sh[64];
   if (threadIdx.x < 64) amax_sh[threadIdx.x] = 0;
@@ -206,6 +208,24 @@ __global__ __launch_bounds__(MAXT) void encode_dynamic_kernel(const uint16_t* __
     ent[t] = (ch << 8) | (__float_as_uint(r) & 0xFFu);
 #pragma unroll
     for (int w = 0; w < B / 32; ++w) mw[w] |= ((ch >> 5) == static_cast<uint32_t>(w)) ? (1u << (ch & 31u)) : 0u;
+  }
+  if (hi_dense) {
+    // Matrix-core-ready image of the bank's high part: zeros, then the k codes scattered to their
+    // channels (even channels of a group of 32 first, then the odd ones).  The scatter goes through
+    // LDS, where a lane can address bytes dynamically; chunk c of lane t sits at (c * blockDim + t) * 16.
+    const int nt = blockDim.x, t = threadIdx.x;
+#pragma unroll
+    for (int ch16 = 0; ch16 < B / 16; ++ch16)
+      *reinterpret_cast<uint4*>(dense_stage + (ch16 * nt + t) * 16) = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < KT; ++i) {
+      const uint32_t ch = ent[i] >> 8;
+      const uint32_t off = (ch & ~31u) + ((ch & 1u) << 4) + ((ch & 31u) >> 1);
+      dense_stage[((off >> 4) * nt + t) * 16 + (off & 15u)] = static_cast<char>(ent[i] & 0xFFu);
+    }
+    uint4* hd = reinterpret_cast<uint4*>(hi_dense + c.row * K + static_cast<int64_t>(c.g) * B);
+#pragma unroll
+    for (int ch16 = 0; ch16 < B / 16; ++ch16) hd[ch16] = *reinterpret_cast<const uint4*>(dense_stage + (ch16 * nt + t) * 16);
   }
   bitonic_sort_desc<KT>(ent);  // descending channel; read back reversed
   uint32_t hv[(KT + 3) / 4];
@@ -382,6 +402,20 @@ __global__ __launch_bounds__(256) void weight_prepack_kernel(int N, int K, int B
   out[idx] = static_cast<uint8_t>(res);
 }
 
+template <int B, int KT, int MAXT>
+int launch_dyn_t(const sq_params& p, const uint16_t* x, int64_t ldx, const sq_act& o, hipStream_t st, int G, int R,
+                 int threads, int blocks) {
+  const size_t lds = o.hi_dense ? static_cast<size_t>(threads) * B : 0;
+  if (lds > 32768) {  // only very long rows with bank 128: ask for the larger dynamic LDS window
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(encode_dynamic_kernel<B, KT, MAXT>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
+      return SQ_ERR_LAUNCH;
+  }
+  hipLaunchKernelGGL((encode_dynamic_kernel<B, KT, MAXT>), dim3(blocks), dim3(threads), lds, st, x, ldx, p.M, p.K, G, R,
+                     o.d_lo, o.hi_val, o.mask, o.scale_lo, o.scale_hi, o.hi_dense);
+  return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
 template <int B, int KT>
 int launch_dyn(const sq_params& p, const uint16_t* x, int64_t ldx, const sq_act& o, hipStream_t st) {
   const int G = p.K / B;
@@ -390,14 +424,8 @@ int launch_dyn(const sq_params& p, const uint16_t* x, int64_t ldx, const sq_act&
   if (R > 32) R = 32;
   const int threads = ((R * G + 63) / 64) * 64;
   const int blocks = (p.M + R - 1) / R;
-  if (threads <= 256) {
-    hipLaunchKernelGGL((encode_dynamic_kernel<B, KT, 256>), dim3(blocks), dim3(threads), 0, st, x, ldx, p.M, p.K, G, R,
-                       o.d_lo, o.hi_val, o.mask, o.scale_lo, o.scale_hi);
-  } else {
-    hipLaunchKernelGGL((encode_dynamic_kernel<B, KT, 512>), dim3(blocks), dim3(threads), 0, st, x, ldx, p.M, p.K, G, R,
-                       o.d_lo, o.hi_val, o.mask, o.scale_lo, o.scale_hi);
-  }
-  return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+  if (threads <= 256) return launch_dyn_t<B, KT, 256>(p, x, ldx, o, st, G, R, threads, blocks);
+  return launch_dyn_t<B, KT, 512>(p, x, ldx, o, st, G, R, threads, blocks);
 }
 
 template <int B>

@@ -48,7 +48,7 @@ def test_sizes(L):
     # 0.75 bytes per element + two scales per row (dense low part, compact high part, explicit mask)
     assert nb.total == 4096 * 4096 * 3 // 4 + 2 * 4096 * 4
     assert sq.sq_gemm_workspace_bytes(p) == 4096 * 4096
-    assert sq.sq_linear_workspace_bytes(p) >= nb.total + 4096 * 4096
+    assert sq.sq_linear_workspace_bytes(p) >= nb.total + 4096 * 4096  # an sq_act plus its hi_dense image
     assert sq.sq_weight_prepack_bytes(p) == 0
     ps = sq.params(4096, 11008, 4096, 64, 8, mode=sq.SQ_STATIC)
     assert sq.sq_weight_prepack_bytes(ps) == 4096 * (11008 // 64 * 8) // 2
@@ -60,7 +60,7 @@ FAKE = 0x10000  # aligned, never dereferenced: every call below must fail before
 
 
 def _encode(L, p, x=FAKE, ldx=None, mask=None, act=None):
-    a = act if act is not None else sq.sq_act(FAKE, FAKE, FAKE, FAKE, FAKE)
+    a = act if act is not None else sq.sq_act(FAKE, FAKE, FAKE, FAKE, FAKE, None)
     return L.sq_encode(ctypes.byref(p), x, p.K if ldx is None else ldx, mask, ctypes.byref(a), None)
 
 
@@ -82,7 +82,7 @@ def test_bad_params_are_refused(L, kw, code):
     assert _encode(L, p) == code
     assert L.sq_act_bytes(ctypes.byref(p), None, None, None, None) == 0
     w = sq.sq_weight(FAKE, FAKE, FAKE)
-    a = sq.sq_act(FAKE, FAKE, FAKE, FAKE, FAKE)
+    a = sq.sq_act(FAKE, FAKE, FAKE, FAKE, FAKE, None)
     assert L.sq_gemm(ctypes.byref(p), ctypes.byref(a), ctypes.byref(w), FAKE, base["N"], None, None, FAKE, 1 << 40, None) == code
     assert L.sq_linear(ctypes.byref(p), FAKE, base["K"], None, ctypes.byref(w), FAKE, base["N"], FAKE, 1 << 40, None) == code
 
@@ -90,17 +90,19 @@ def test_bad_params_are_refused(L, kw, code):
 def test_null_alignment_and_leading_dimension(L):
     p = sq.params(16, 512, 512, 64, 8, out_dtype=0)
     assert _encode(L, p, x=None) == -1
-    assert _encode(L, p, act=sq.sq_act(FAKE, None, FAKE, FAKE, FAKE)) == -1
+    assert _encode(L, p, act=sq.sq_act(FAKE, None, FAKE, FAKE, FAKE, None)) == -1
     assert _encode(L, p, x=FAKE + 2) == -4
-    assert _encode(L, p, act=sq.sq_act(FAKE + 4, FAKE, FAKE, FAKE, FAKE)) == -4
+    assert _encode(L, p, act=sq.sq_act(FAKE + 4, FAKE, FAKE, FAKE, FAKE, None)) == -4
     assert _encode(L, p, ldx=511) == -2
     assert _encode(L, p, ldx=516) == -4  # rows would not stay 16-byte aligned
     ps = sq.params(16, 512, 512, 64, 8, mode=1)
     assert _encode(L, ps, mask=None) == -3  # static mode needs a mask
     w = sq.sq_weight(FAKE, FAKE, None)
-    a = sq.sq_act(FAKE, FAKE, FAKE, FAKE, FAKE)
+    a = sq.sq_act(FAKE, FAKE, FAKE, FAKE, FAKE, None)
     args = (ctypes.byref(a), ctypes.byref(w), FAKE, 512, None, None)
-    assert L.sq_gemm(ctypes.byref(p), *args, None, 0, None) == -7
+    assert L.sq_gemm(ctypes.byref(p), *args, None, 0, None) == -7   # no hi_dense and no workspace
+    a_hd = sq.sq_act(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE + 8)
+    assert L.sq_gemm(ctypes.byref(p), ctypes.byref(a_hd), ctypes.byref(w), FAKE, 512, None, None, None, 0, None) == -4
     assert L.sq_gemm(ctypes.byref(p), *args, FAKE, 16 * 512 - 1, None) == -7
     assert L.sq_gemm(ctypes.byref(p), ctypes.byref(a), ctypes.byref(w), FAKE, 511, None, None, FAKE, 1 << 30, None) == -2
     assert L.sq_gemm(ctypes.byref(p), ctypes.byref(a), ctypes.byref(w), None, 512, None, None, FAKE, 1 << 30, None) == -1

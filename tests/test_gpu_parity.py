@@ -224,3 +224,44 @@ def test_dense_w4a8_reference_kernel():
     acc = a.astype(np.int64) @ w.astype(np.int64).T
     want = (acc.astype(np.float32) * sa[:, None]).astype(np.float32) * sw[None, :]
     assert np.array_equal(y.host(np.float32).reshape(M, N), want.astype(np.float32))
+
+
+def expected_hi_dense(enc):
+    """The documented image: INT8 codes at their channels, zero elsewhere; inside every group of
+    32 channels the even channels come first, then the odd ones."""
+    M, K = enc.M, enc.K
+    dense = np.zeros((M, K), np.int8)
+    flags = ((enc.mask[:, :, None] >> np.arange(32, dtype=np.uint32)[None, None, :]) & 1).reshape(M, K).astype(bool)
+    for m in range(M):
+        dense[m, flags[m]] = enc.hi_val[m].reshape(-1)
+    g = dense.reshape(M, K // 32, 32)
+    return np.concatenate([g[:, :, 0::2], g[:, :, 1::2]], axis=2).reshape(M, K)
+
+
+@pytest.mark.parametrize("K,bank,topk", [(1024, 64, 8), (512, 32, 4), (2048, 128, 32), (11008, 64, 8)])
+def test_hi_dense_image_from_encoder_and_from_gemm_workspace(K, bank, topk):
+    _say(f"hi_dense K={K} bank={bank} topk={topk}")
+    M, N = 19, 64
+    bits, wq, sw = random_case(4000 + K, M, K, N)
+    enc = oracle.encode(bits, bank, topk)
+    want = expected_hi_dense(enc)
+    p = sq.params(M, K, N, bank, topk, out_dtype=sq.SQ_OUT_F32)
+    # written by the encoder
+    act = sq.Act(p, with_hi_dense=True)
+    sq.sq_encode(p, dev(bits), act)
+    torch.cuda.synchronize()
+    assert_encoding_equal(act, enc)
+    assert np.array_equal(act.hi_dense.cpu().numpy().reshape(M, K), want)
+    # built by sq_gemm in its workspace when the caller has none
+    act2 = sq.Act(p)
+    sq.sq_encode(p, dev(bits), act2)
+    ws = torch.empty(sq.sq_gemm_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    y1 = torch.empty(M * N, dtype=torch.float32, device="cuda")
+    y2 = torch.empty(M * N, dtype=torch.float32, device="cuda")
+    w = sq.weight(dev(wq), dev(sw))
+    sq.sq_gemm(p, act2, w, y1, ws)
+    sq.sq_gemm(p, act, w, y2, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(ws[:M * K].cpu().numpy().view(np.int8).reshape(M, K), want)
+    assert torch.equal(y1, y2)
+    assert np.array_equal(y1.cpu().numpy().reshape(M, N).view(np.uint32), oracle.gemm(enc, wq, sw).y32.view(np.uint32))
