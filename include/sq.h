@@ -71,8 +71,9 @@ typedef struct {
   float *scale_lo;  /* [M] per-token scale of the low part  (largest low magnitude / 7) */
   float *scale_hi;  /* [M] per-token scale of the high part (largest high magnitude / 127) */
   int8_t *hi_dense; /* optional (may be NULL), dynamic mode only: [M, K] matrix-core-ready image of the high part,
-                       a pure function of (hi_val, mask): the INT8 codes at their channels, 0 elsewhere, the 32
-                       channels of every group stored even channels first, then odd channels.  sq_encode writes
+                       a pure function of (hi_val, mask): the INT8 codes at their channels, 0 elsewhere, the 8
+                       channels of every group stored even channels first, then odd channels (channel 8q+e sits
+                       at byte 8q + 4*(e%2) + e/2).  sq_encode writes
                        it when the pointer is set; sq_gemm uses it when set and otherwise builds it in its
                        workspace.  Not part of the format: a cache that saves sq_gemm one pass. */
 } sq_act;

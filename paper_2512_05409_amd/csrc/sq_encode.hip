@@ -211,8 +211,8 @@ __global__ __launch_bounds__(MAXT) void encode_dynamic_kernel(const uint16_t* __
   }
   if (hi_dense) {
     // Matrix-core-ready image of the bank's high part: zeros, then the k codes scattered to their
-    // channels (even channels of a group of 32 first, then the odd ones).  The scatter goes through
-    // LDS, where a lane can address bytes dynamically; chunk c of lane t sits at (c * blockDim + t) * 16.
+    // channels (inside every group of 8 channels: the even ones, then the odd ones).  The scatter goes
+    // through LDS, where a lane can address bytes dynamically; chunk c of lane t sits at (c * blockDim + t) * 16.
     const int nt = blockDim.x, t = threadIdx.x;
 #pragma unroll
     for (int ch16 = 0; ch16 < B / 16; ++ch16)
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(MAXT) void encode_dynamic_kernel(const uint16_t* __
 #pragma unroll
     for (int i = 0; i < KT; ++i) {
       const uint32_t ch = ent[i] >> 8;
-      const uint32_t off = (ch & ~31u) + ((ch & 1u) << 4) + ((ch & 31u) >> 1);
+      const uint32_t off = (ch & ~7u) | ((ch & 1u) << 2) | ((ch & 7u) >> 1);
       dense_stage[((off >> 4) * nt + t) * 16 + (off & 15u)] = static_cast<char>(ent[i] & 0xFFu);
     }
     uint4* hd = reinterpret_cast<uint4*>(hi_dense + c.row * K + static_cast<int64_t>(c.g) * B);
@@ -329,9 +329,9 @@ __global__ __launch_bounds__(MAXT) void encode_static_kernel(const uint16_t* __r
   for (int i = 0; i < B / 32; ++i) ddst[i] = make_uint4(dl[4 * i], dl[4 * i + 1], dl[4 * i + 2], dl[4 * i + 3]);
 }
 
-// (hi_val, mask) -> zero-padded INT8 image of the high part.  Inside every group of 32 channels the
+// (hi_val, mask) -> zero-padded INT8 image of the high part.  Inside every group of 8 channels the
 // bytes are stored even channels first, then odd channels: the order in which the GEMM kernel's
-// nibble unpack delivers a weight row.
+// nibble widening delivers a weight row.
 __global__ __launch_bounds__(256) void expand_hi_kernel(const int8_t* __restrict__ hi_val,
                                                         const uint32_t* __restrict__ mask, int64_t total, int K,
                                                         int B, int KT, int8_t* __restrict__ out) {
@@ -356,7 +356,7 @@ __global__ __launch_bounds__(256) void expand_hi_kernel(const int8_t* __restrict
   while (word && left > 0) {
     const int e = __ffs(static_cast<int>(word)) - 1;
     word &= word - 1;
-    myb[(e & 1) * 16 + (e >> 1)] = *src++;
+    myb[(e & ~7) | ((e & 1) << 2) | ((e & 7) >> 1)] = *src++;
     --left;
   }
   uint4* dst = reinterpret_cast<uint4*>(out + row * K + static_cast<int64_t>(wg) * 32);
@@ -365,8 +365,8 @@ __global__ __launch_bounds__(256) void expand_hi_kernel(const int8_t* __restrict
 }
 
 // Static mode: compact copy of the high channels' weight columns.  Output row n holds k_hi_padded
-// codes (zero beyond (K/B)*KT); inside every group of 32 codes byte j carries code j in its low and
-// code j+16 in its high nibble, so that the GEMM kernel's unpack yields codes 0..15 and 16..31 in order.
+// codes (zero beyond (K/B)*KT); byte j of every group of 8 codes (4 bytes) carries code j in its low and
+// code j+4 in its high nibble, so that the GEMM kernel's nibble widening yields the codes in natural order.
 __global__ __launch_bounds__(256) void weight_prepack_kernel(int N, int K, int B, int KT, int k_hi_padded,
                                                              const uint8_t* __restrict__ wq,
                                                              const uint32_t* __restrict__ mask,
@@ -376,11 +376,11 @@ __global__ __launch_bounds__(256) void weight_prepack_kernel(int N, int K, int B
   if (idx >= static_cast<int64_t>(N) * bytes_per_row) return;
   const int64_t n = idx / bytes_per_row;
   const int byte = static_cast<int>(idx - n * bytes_per_row);
-  const int grp = byte / 16, j = byte % 16;
+  const int grp = byte / 4, j = byte % 4;
   const int k_hi = mask ? (K / B) * KT : K;
   uint32_t res = 0;
   for (int h = 0; h < 2; ++h) {
-    const int t = grp * 32 + j + 16 * h;  // index into the compact list of high channels
+    const int t = grp * 8 + j + 4 * h;  // index into the compact list of high channels
     uint32_t code = 0;
     if (!mask) {  // every channel, in order (plain W4A8 reference)
       code = (wq[n * (K / 2) + (t >> 1)] >> ((t & 1) * 4)) & 0xFu;

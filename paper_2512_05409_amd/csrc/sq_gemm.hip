@@ -2,161 +2,201 @@
 // matrix cores of gfx950, with the dequantising epilogue fused.
 //
 // CDNA4 has no INT4 matrix instruction, so both products run on v_mfma_i32_32x32x32_i8.
-// INT4 codes are widened on the way into LDS without sign extension: a nibble placed in the
-// HIGH four bits of a byte is the signed byte 16*code, so
-//     lo_bytes = (dword << 4) & 0xF0F0F0F0      (codes 0,2,4,6 of the 8 in a dword)
-//     hi_bytes =  dword       & 0xF0F0F0F0      (codes 1,3,5,7)
+// INT4 codes stay packed (two per byte) from HBM through LDS and are widened in registers just
+// before the matrix instruction, without sign extension: a nibble placed in the HIGH four bits
+// of a byte is the signed byte 16*code, so for a dword p of eight codes
+//     (p << 4) & 0xF0F0F0F0   are codes 0,2,4,6 (times 16)      p & 0xF0F0F0F0   are codes 1,3,5,7
 // and the accumulators come out as exact multiples (256x when both operands are widened this
 // way, 16x when only the weights are), shifted back in the epilogue.  Integer addition is
-// order-independent, so the products are bit-exact whatever the K order; both operands simply
-// use the same one: inside a group of 32 channels, the 16 even channels then the 16 odd ones.
+// order-independent, so the products are bit-exact whatever the K order, as long as both operands
+// use the same one.  The order used: a 16-byte chunk of packed codes (32 channels) feeds two
+// consecutive matrix instructions; instruction s (0/1) takes dwords 2s, 2s+1 of the chunk as
+// [evens of dword 2s | odds of dword 2s | evens of dword 2s+1 | odds of dword 2s+1].  The INT8
+// image of the high part is stored in exactly that byte order (see sq_act::hi_dense).
 //
-// LDS holds operands in matrix-instruction order: for every (32-row block, 32-channel group) a
-// 1 KB block whose 16-byte chunk c belongs to lane c of the wave that will issue the MFMA
-// (lane = row % 32 + 32 * half).  A wave's operand read is then one contiguous 1 KB ds_read_b128.
+// Work split: a workgroup of 4 waves computes 128 tokens x 256 output channels; a wave computes
+// 64 tokens x 128 channels for BOTH products (2 x 2x4 tiles of 32x32, 256 accumulator registers).
+// A K step of 128 channels is staged through LDS, double buffered.  LDS rows are row-major with
+// the 16-byte chunk index XOR-swizzled by the row, which keeps both the staging stores (4 or 8
+// consecutive lanes per row) and the operand reads (32 consecutive rows per half wave) conflict-free.
 #include "sq_device.h"
 
 namespace sq {
 namespace {
 
-constexpr int BM = 128;   // tokens per workgroup tile
-constexpr int BN = 128;   // output channels per workgroup tile
-constexpr int KS = 128;   // channels per K step
-constexpr int NT = 256;   // threads: 4 waves as 2 (M) x 2 (N), each 64 tokens x 64 channels
-constexpr int KG = KS / 32;
-constexpr int ROT = 4;    // per-group rotation of the chunks inside a 1 KB block (spreads the writers over banks)
-constexpr int OPER_BYTES = (BM / 32) * KG * 1024;  // one operand tile of one stage: 16 KB
-constexpr int STAGE_BYTES = 3 * OPER_BYTES;        // A_lo | A_hi | B
-constexpr int LDS_BYTES = 2 * STAGE_BYTES;
-static_assert(BM == BN, "operand tiles share one size");
-
-__device__ __forceinline__ int frag_offset(int row, int kg, int half) {
-  return (((row >> 5) * KG + kg) << 10) + ((((row & 31) + 32 * half + ROT * kg) & 63) << 4);
-}
-
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
-struct Staging {
-  v4u a_lo[2];
-  v4u a_hi[4];
-  v4u b[2];
+constexpr int KS = 128;  // channels per K step
+constexpr int NT = 256;  // threads per workgroup
+
+template <int BM_, int BN_>
+struct Tile {
+  static constexpr int BM = BM_;              // tokens per workgroup
+  static constexpr int BN = BN_;              // output channels per workgroup
+  static constexpr int WM = BM / 2;           // tokens per wave (waves are 2 x 2)
+  static constexpr int WN = BN / 2;           // channels per wave
+  static constexpr int TI = WM / 32;          // 32-row tiles per wave along M
+  static constexpr int TJ = WN / 32;          // along N
+  static constexpr int A_LO = 0;              // [BM][64 B]   packed INT4
+  static constexpr int A_HI = BM * 64;        // [BM][128 B]  INT8
+  static constexpr int B_OFF = A_HI + BM * 128;  // [BN][64 B] packed INT4
+  static constexpr int STAGE = B_OFF + BN * 64;
+  static constexpr int LDS_BYTES = 2 * STAGE;
 };
 
-// Operand sources of one K loop.  Row pointers are already clamped to valid rows.
-template <bool LO, bool HI>
+// Byte offset of 16-byte chunk c of a row inside an operand tile.
+__device__ __forceinline__ int off4(int row, int c) { return (row << 6) + (((c ^ (row >> 2)) & 3) << 4); }   // 4 chunks / row
+__device__ __forceinline__ int off8(int row, int c) { return (row << 7) + (((c ^ (row >> 1)) & 7) << 4); }   // 8 chunks / row
+
+template <typename T>
+struct Staging {
+  v4u a_lo[T::BM * 4 / NT];
+  v4u a_hi[T::BM * 8 / NT];
+  v4u b[T::BN * 4 / NT];
+};
+
+// Operand sources of one K loop.  LO: the packed low part is an operand; HI: an INT8 operand
+// (the zero-padded image of the high part, or the compact high codes) is.
+template <typename T, bool LO, bool HI>
 struct Loader {
-  const uint8_t* a_lo;   // + row * lda_lo
+  const uint8_t* a_lo;
   int64_t lda_lo;
   const int8_t* a_hi;
   int64_t lda_hi;
   const uint8_t* b;
   int64_t ldb;
-  int kext;              // channels in this loop (multiple of 32)
+  int kext;  // channels in this loop (multiple of 32)
   int m0, n0, M, N;
 
-  // Loads are unconditional from an address clamped into the operand (rows past the edge repeat the
-  // last row and are never stored; channel groups past kext read the last group and are zeroed).
-  __device__ __forceinline__ void load(Staging& s, int k0) const {
+  // Loads are unconditional from an address clamped into the operand: rows past the edge repeat the
+  // last row and are never stored; chunks past kext (only possible in the last, partial K step) read
+  // the last chunk and are zeroed when they are written to LDS.
+  __device__ __forceinline__ void load(Staging<T>& s, int k0) const {
     const int tid = threadIdx.x;
-    const v4u zero = {0u, 0u, 0u, 0u};
+    if (LO) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = tid + NT * i;
-      const int row = c >> 2, kg = c & 3;
-      const int k = k0 + kg * 32;
-      const bool ok = k < kext;
-      const int kc = ok ? k : kext - 32;
-      if (LO) {
+      for (int i = 0; i < T::BM * 4 / NT; ++i) {
+        const int idx = tid + NT * i, row = idx >> 2, c = idx & 3;
+        const int k = min(k0 + c * 32, kext - 32);
         const int m = min(m0 + row, M - 1);
-        const v4u v = *reinterpret_cast<const v4u*>(a_lo + m * lda_lo + (kc >> 1));
-        s.a_lo[i] = ok ? v : zero;
+        s.a_lo[i] = *reinterpret_cast<const v4u*>(a_lo + m * lda_lo + (k >> 1));
       }
-      const int n = min(n0 + row, N - 1);
-      const v4u v = *reinterpret_cast<const v4u*>(b + n * ldb + (kc >> 1));
-      s.b[i] = ok ? v : zero;
     }
     if (HI) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int c = tid + NT * i;
-        const int row = c >> 3, ch = c & 7;
-        const int k = k0 + ch * 16;
-        const bool ok = k < kext;
-        const int kc = ok ? k : kext - 16;
+      for (int i = 0; i < T::BM * 8 / NT; ++i) {
+        const int idx = tid + NT * i, row = idx >> 3, c = idx & 7;
+        const int k = min(k0 + c * 16, kext - 16);
         const int m = min(m0 + row, M - 1);
-        const v4u v = *reinterpret_cast<const v4u*>(a_hi + m * lda_hi + kc);
-        s.a_hi[i] = ok ? v : zero;
+        s.a_hi[i] = *reinterpret_cast<const v4u*>(a_hi + m * lda_hi + k);
       }
+    }
+#pragma unroll
+    for (int i = 0; i < T::BN * 4 / NT; ++i) {
+      const int idx = tid + NT * i, row = idx >> 2, c = idx & 3;
+      const int k = min(k0 + c * 32, kext - 32);
+      const int n = min(n0 + row, N - 1);
+      s.b[i] = *reinterpret_cast<const v4u*>(b + n * ldb + (k >> 1));
     }
   }
 
-  __device__ __forceinline__ void store(const Staging& s, char* stage) const {
+  __device__ __forceinline__ void store(Staging<T>& s, char* stage, int k0) const {
     const int tid = threadIdx.x;
+    if (k0 + KS > kext) {  // partial K step (uniform branch): zero what lies past the end
+      const v4u zero = {0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = tid + NT * i;
-      const int row = c >> 2, kg = c & 3;
-      if (LO) {
-        const v4u v = s.a_lo[i];
-        *reinterpret_cast<v4u*>(stage + frag_offset(row, kg, 0)) = (v << 4) & 0xF0F0F0F0u;
-        *reinterpret_cast<v4u*>(stage + frag_offset(row, kg, 1)) = v & 0xF0F0F0F0u;
+      for (int i = 0; i < T::BM * 4 / NT; ++i)
+        if (LO && k0 + ((tid + NT * i) & 3) * 32 >= kext) s.a_lo[i] = zero;
+#pragma unroll
+      for (int i = 0; i < T::BM * 8 / NT; ++i)
+        if (HI && k0 + ((tid + NT * i) & 7) * 16 >= kext) s.a_hi[i] = zero;
+#pragma unroll
+      for (int i = 0; i < T::BN * 4 / NT; ++i)
+        if (k0 + ((tid + NT * i) & 3) * 32 >= kext) s.b[i] = zero;
+    }
+    if (LO) {
+#pragma unroll
+      for (int i = 0; i < T::BM * 4 / NT; ++i) {
+        const int idx = tid + NT * i;
+        *reinterpret_cast<v4u*>(stage + T::A_LO + off4(idx >> 2, idx & 3)) = s.a_lo[i];
       }
-      const v4u v = s.b[i];
-      *reinterpret_cast<v4u*>(stage + 2 * OPER_BYTES + frag_offset(row, kg, 0)) = (v << 4) & 0xF0F0F0F0u;
-      *reinterpret_cast<v4u*>(stage + 2 * OPER_BYTES + frag_offset(row, kg, 1)) = v & 0xF0F0F0F0u;
     }
     if (HI) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int c = tid + NT * i;
-        const int row = c >> 3, ch = c & 7;
-        *reinterpret_cast<v4u*>(stage + OPER_BYTES + frag_offset(row, ch >> 1, ch & 1)) = s.a_hi[i];
+      for (int i = 0; i < T::BM * 8 / NT; ++i) {
+        const int idx = tid + NT * i;
+        *reinterpret_cast<v4u*>(stage + T::A_HI + off8(idx >> 3, idx & 7)) = s.a_hi[i];
       }
+    }
+#pragma unroll
+    for (int i = 0; i < T::BN * 4 / NT; ++i) {
+      const int idx = tid + NT * i;
+      *reinterpret_cast<v4u*>(stage + T::B_OFF + off4(idx >> 2, idx & 3)) = s.b[i];
     }
   }
 };
 
-template <bool LO, bool HI>
-__device__ __forceinline__ void compute_stage(const char* stage, int wm, int wn, int lane, v16i (&acc_lo)[2][2],
-                                              v16i (&acc_hi)[2][2]) {
+// One packed chunk (32 INT4 codes) -> the INT8 operands of two consecutive matrix instructions.
+__device__ __forceinline__ void widen(const v4u p, v4i& s0, v4i& s1) {
+  const v4u e = (p << 4) & 0xF0F0F0F0u;
+  const v4u o = p & 0xF0F0F0F0u;
+  s0 = v4i{static_cast<int>(e[0]), static_cast<int>(o[0]), static_cast<int>(e[1]), static_cast<int>(o[1])};
+  s1 = v4i{static_cast<int>(e[2]), static_cast<int>(o[2]), static_cast<int>(e[3]), static_cast<int>(o[3])};
+}
+
+template <typename T, bool LO, bool HI>
+__device__ __forceinline__ void compute_stage(const char* stage, int wm, int wn, int lane, v16i (&acc_lo)[T::TI][T::TJ],
+                                              v16i (&acc_hi)[T::TI][T::TJ]) {
+  const int r = lane & 31, h = lane >> 5;
 #pragma unroll
-  for (int kg = 0; kg < KG; ++kg) {
-    const int chunk = ((lane + ROT * kg) & 63) << 4;
-    v4i bf[2], alo[2], ahi[2];
+  for (int g = 0; g < KS / 64; ++g) {
+    v4i bw[T::TJ][2], alo[T::TI][2], ahi[T::TI][2];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-      bf[j] = *reinterpret_cast<const v4i*>(stage + 2 * OPER_BYTES + (((wn * 2 + j) * KG + kg) << 10) + chunk);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      if (LO) alo[i] = *reinterpret_cast<const v4i*>(stage + (((wm * 2 + i) * KG + kg) << 10) + chunk);
-      if (HI) ahi[i] = *reinterpret_cast<const v4i*>(stage + OPER_BYTES + (((wm * 2 + i) * KG + kg) << 10) + chunk);
+    for (int j = 0; j < T::TJ; ++j) {
+      const v4u p = *reinterpret_cast<const v4u*>(stage + T::B_OFF + off4(wn * T::WN + j * 32 + r, 2 * g + h));
+      widen(p, bw[j][0], bw[j][1]);
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < T::TI; ++i) {
+      const int row = wm * T::WM + i * 32 + r;
+      if (LO) {
+        const v4u p = *reinterpret_cast<const v4u*>(stage + T::A_LO + off4(row, 2 * g + h));
+        widen(p, alo[i][0], alo[i][1]);
+      }
+      if (HI) {
+        ahi[i][0] = *reinterpret_cast<const v4i*>(stage + T::A_HI + off8(row, 4 * g + 2 * h));
+        ahi[i][1] = *reinterpret_cast<const v4i*>(stage + T::A_HI + off8(row, 4 * g + 2 * h + 1));
+      }
+    }
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        if (LO) acc_lo[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo[i], bf[j], acc_lo[i][j], 0, 0, 0);
-        if (HI) acc_hi[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi[i], bf[j], acc_hi[i][j], 0, 0, 0);
+    for (int s = 0; s < 2; ++s) {
+#pragma unroll
+      for (int i = 0; i < T::TI; ++i) {
+#pragma unroll
+        for (int j = 0; j < T::TJ; ++j) {
+          if (LO) acc_lo[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo[i][s], bw[j][s], acc_lo[i][j], 0, 0, 0);
+          if (HI) acc_hi[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi[i][s], bw[j][s], acc_hi[i][j], 0, 0, 0);
+        }
       }
     }
   }
 }
 
-template <bool LO, bool HI>
-__device__ __forceinline__ void k_loop(const Loader<LO, HI>& ld, char* lds, int wm, int wn, int lane,
-                                       v16i (&acc_lo)[2][2], v16i (&acc_hi)[2][2]) {
+template <typename T, bool LO, bool HI>
+__device__ __forceinline__ void k_loop(const Loader<T, LO, HI>& ld, char* lds, int wm, int wn, int lane,
+                                       v16i (&acc_lo)[T::TI][T::TJ], v16i (&acc_hi)[T::TI][T::TJ]) {
   const int steps = (ld.kext + KS - 1) / KS;
-  Staging s;
+  Staging<T> s;
   ld.load(s, 0);
-  ld.store(s, lds);
+  ld.store(s, lds, 0);
   __syncthreads();
   for (int kt = 0; kt < steps; ++kt) {
-    char* cur = lds + (kt & 1) * STAGE_BYTES;
-    char* nxt = lds + ((kt + 1) & 1) * STAGE_BYTES;
+    char* cur = lds + (kt & 1) * T::STAGE;
+    char* nxt = lds + ((kt + 1) & 1) * T::STAGE;
     const bool more = (kt + 1) < steps;
     if (more) ld.load(s, (kt + 1) * KS);
-    compute_stage<LO, HI>(cur, wm, wn, lane, acc_lo, acc_hi);
-    if (more) ld.store(s, nxt);
+    compute_stage<T, LO, HI>(cur, wm, wn, lane, acc_lo, acc_hi);
+    if (more) ld.store(s, nxt, (kt + 1) * KS);
     __syncthreads();
   }
 }
@@ -167,21 +207,45 @@ __device__ __forceinline__ uint16_t bf16_rne(float f) {
   return static_cast<uint16_t>(u >> 16);
 }
 
+// Maps the linear workgroup id to a tile so that (a) the workgroups resident on one XCD at a time
+// (ids congruent mod 8 go to the same XCD) cover a compact 4 x 8 patch of tiles and share operand
+// tiles in that XCD's L2, and (b) every XCD walks its own contiguous range of the tile order.
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn) {
+  const int total = tiles_m * tiles_n;
+  const int id = blockIdx.x;
+  const int per_xcd = (total + 7) / 8;
+  const int lin = (id & 7) * per_xcd + (id >> 3);  // position in the tile order
+  if (lin >= total) {  // the grid is rounded up to a multiple of 8: the overhang does nothing
+    tm = -1;
+    tn = -1;
+    return;
+  }
+  constexpr int BAND = 4;  // tile rows walked together
+  const int band = lin / (BAND * tiles_n);
+  const int within = lin - band * (BAND * tiles_n);
+  const int rows_here = min(BAND, tiles_m - band * BAND);
+  tn = within / rows_here;
+  tm = band * BAND + within - tn * rows_here;
+}
+
 // MODE 0: dynamic (low + zero-padded high in one K loop); 1: static (low loop over K, then the
 // compact high loop over K_hi); 2: high loop only (plain W4A8 reference).
-template <int MODE>
+template <typename T, int MODE>
 __global__ __launch_bounds__(NT) void gemm_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  int tm, tn;
+  tile_of_block((g.M + T::BM - 1) / T::BM, (g.N + T::BN - 1) / T::BN, tm, tn);
+  if (tm < 0) return;
+  const int m0 = tm * T::BM, n0 = tn * T::BN;
 
-  v16i acc_lo[2][2], acc_hi[2][2];
+  v16i acc_lo[T::TI][T::TJ], acc_hi[T::TI][T::TJ];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < T::TI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < T::TJ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         acc_lo[i][j][r] = 0;
@@ -189,30 +253,30 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmArgs g) {
       }
 
   if (MODE == 0) {
-    Loader<true, true> ld{g.a_lo, g.K / 2, g.a_hi_dense, g.K, g.wq, g.K / 2, g.K, m0, n0, g.M, g.N};
-    k_loop<true, true>(ld, lds, wm, wn, lane, acc_lo, acc_hi);
+    Loader<T, true, true> ld{g.a_lo, g.K / 2, g.a_hi_dense, g.K, g.wq, g.K / 2, g.K, m0, n0, g.M, g.N};
+    k_loop<T, true, true>(ld, lds, wm, wn, lane, acc_lo, acc_hi);
   } else if (MODE == 1) {
-    Loader<true, false> l1{g.a_lo, g.K / 2, nullptr, 0, g.wq, g.K / 2, g.K, m0, n0, g.M, g.N};
-    k_loop<true, false>(l1, lds, wm, wn, lane, acc_lo, acc_hi);
-    Loader<false, true> l2{nullptr, 0, g.a_hi_compact, g.lda_hi_compact, g.w_hi, g.K_hi / 2, g.K_hi, m0, n0, g.M, g.N};
-    k_loop<false, true>(l2, lds, wm, wn, lane, acc_lo, acc_hi);
+    Loader<T, true, false> l1{g.a_lo, g.K / 2, nullptr, 0, g.wq, g.K / 2, g.K, m0, n0, g.M, g.N};
+    k_loop<T, true, false>(l1, lds, wm, wn, lane, acc_lo, acc_hi);
+    Loader<T, false, true> l2{nullptr, 0, g.a_hi_compact, g.lda_hi_compact, g.w_hi, g.K_hi / 2, g.K_hi, m0, n0, g.M, g.N};
+    k_loop<T, false, true>(l2, lds, wm, wn, lane, acc_lo, acc_hi);
   } else {
-    Loader<false, true> l2{nullptr, 0, g.a_hi_compact, g.lda_hi_compact, g.w_hi, g.K_hi / 2, g.K_hi, m0, n0, g.M, g.N};
-    k_loop<false, true>(l2, lds, wm, wn, lane, acc_lo, acc_hi);
+    Loader<T, false, true> l2{nullptr, 0, g.a_hi_compact, g.lda_hi_compact, g.w_hi, g.K_hi / 2, g.K_hi, m0, n0, g.M, g.N};
+    k_loop<T, false, true>(l2, lds, wm, wn, lane, acc_lo, acc_hi);
   }
 
   // Epilogue: Y = (acc_lo * s_lo[m] + acc_hi * s_hi[m]) * s_w[n], in this order, in fp32.
   // Accumulator register r of lane l of a 32x32 tile is row 8*(r/4) + 4*(l/32) + r%4, column l%32.
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int n = n0 + wn * 64 + j * 32 + (lane & 31);
+  for (int j = 0; j < T::TJ; ++j) {
+    const int n = n0 + wn * T::WN + j * 32 + (lane & 31);
     const bool n_ok = n < g.N;
     const float sw = n_ok ? g.s_w[n] : 0.0f;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < T::TI; ++i) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const int m = m0 + wm * T::WM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         if (n_ok && m < g.M) {
           const int lo = acc_lo[i][j][r] >> 8;  // exact: both operands carried a factor 16
           const int hi = acc_hi[i][j][r] >> 4;  // exact: the weights carried a factor 16
@@ -230,7 +294,7 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmArgs g) {
   }
 }
 
-template <int MODE>
+template <typename T, int MODE>
 int launch_mode(const GemmArgs& g, hipStream_t st) {
   // The kernel needs more dynamic LDS than the default limit; raising it is per device and
   // idempotent, so a race between threads only repeats the call.
@@ -238,22 +302,24 @@ int launch_mode(const GemmArgs& g, hipStream_t st) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return SQ_ERR_LAUNCH;
   if (!attr_done[dev]) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<MODE>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            LDS_BYTES) != hipSuccess)
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<T, MODE>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES) != hipSuccess)
       return SQ_ERR_LAUNCH;
     attr_done[dev] = true;
   }
-  dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM);
-  hipLaunchKernelGGL(gemm_kernel<MODE>, grid, dim3(NT), LDS_BYTES, st, g);
+  const int tiles = ((g.N + T::BN - 1) / T::BN) * ((g.M + T::BM - 1) / T::BM);
+  const int blocks = (tiles + 7) / 8 * 8;
+  hipLaunchKernelGGL((gemm_kernel<T, MODE>), dim3(blocks), dim3(NT), T::LDS_BYTES, st, g);
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
 }  // namespace
 
 int launch_gemm(const GemmArgs& g, hipStream_t st) {
-  if (g.a_lo && g.a_hi_dense) return launch_mode<0>(g, st);
-  if (g.a_lo && g.a_hi_compact) return launch_mode<1>(g, st);
-  if (!g.a_lo && g.a_hi_compact) return launch_mode<2>(g, st);
+  typedef Tile<128, 256> Big;
+  if (g.a_lo && g.a_hi_dense) return launch_mode<Big, 0>(g, st);
+  if (g.a_lo && g.a_hi_compact) return launch_mode<Big, 1>(g, st);
+  if (!g.a_lo && g.a_hi_compact) return launch_mode<Big, 2>(g, st);
   return SQ_ERR_UNSUPPORTED;
 }
 

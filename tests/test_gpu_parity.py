@@ -228,13 +228,13 @@ def test_dense_w4a8_reference_kernel():
 
 def expected_hi_dense(enc):
     """The documented image: INT8 codes at their channels, zero elsewhere; inside every group of
-    32 channels the even channels come first, then the odd ones."""
+    8 channels the even channels come first, then the odd ones."""
     M, K = enc.M, enc.K
     dense = np.zeros((M, K), np.int8)
     flags = ((enc.mask[:, :, None] >> np.arange(32, dtype=np.uint32)[None, None, :]) & 1).reshape(M, K).astype(bool)
     for m in range(M):
         dense[m, flags[m]] = enc.hi_val[m].reshape(-1)
-    g = dense.reshape(M, K // 32, 32)
+    g = dense.reshape(M, K // 8, 8)
     return np.concatenate([g[:, :, 0::2], g[:, :, 1::2]], axis=2).reshape(M, K)
 
 
