@@ -228,6 +228,104 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm,
   tm = band * BAND + within - tn * rows_here;
 }
 
+// Epilogue: Y = (acc_lo * s_lo[m] + acc_hi * s_hi[m]) * s_w[n], in this order, in fp32.
+// Accumulator register r of lane l of a 32x32 tile is row 8*(r/4) + 4*(l/32) + r%4, column l%32, so a
+// lane holds single elements of many rows.  The per-token scales of the workgroup's rows and the
+// finished outputs go through LDS (free after the K loops): every wave transposes 32 rows x WN columns
+// at a time and then stores 16 bytes per lane, whole row segments at once.
+template <typename T, typename OutT>
+__device__ __forceinline__ void epilogue_typed(const GemmArgs& g, char* lds, v16i (&acc_lo)[T::TI][T::TJ],
+                                               v16i (&acc_hi)[T::TI][T::TJ], int m0, int n0, int wm, int wn, int wave,
+                                               int lane) {
+  constexpr int ESZ = sizeof(OutT);
+  constexpr int ROW = T::WN * ESZ + 16;   // padded row of the transposition buffer (bytes)
+  constexpr int PER16 = 16 / ESZ;         // outputs per 16-byte store
+  constexpr int CHUNKS = T::WN / PER16;   // 16-byte chunks per row
+  constexpr int ROWS_PER_PASS = 64 / CHUNKS;
+  static_assert(1024 + 4 * 32 * ROW <= T::LDS_BYTES, "transposition buffers must fit in the stage memory");
+  const int tid = threadIdx.x;
+  float* sc = reinterpret_cast<float*>(lds);  // [0, BM): s_lo, [BM, 2 BM): s_hi   (BM <= 128)
+  char* tb = lds + 1024 + wave * (32 * ROW);
+  if (tid < T::BM) {
+    const int m = min(m0 + tid, g.M - 1);
+    sc[tid] = g.s_lo ? g.s_lo[m] : 0.0f;
+    sc[T::BM + tid] = g.s_hi[m];
+  }
+  __syncthreads();
+  float sw[T::TJ];
+#pragma unroll
+  for (int j = 0; j < T::TJ; ++j) {
+    const int n = n0 + wn * T::WN + j * 32 + (lane & 31);
+    sw[j] = n < g.N ? g.s_w[n] : 0.0f;
+  }
+  const bool vec_ok = (g.ldy % PER16) == 0;  // rows of Y stay 16-byte aligned
+  OutT* yout = reinterpret_cast<OutT*>(g.y);
+#pragma unroll
+  for (int i = 0; i < T::TI; ++i) {
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+      const int rl0 = 8 * rq + 4 * (lane >> 5);  // 4 consecutive rows of the 32: registers 4 rq + e
+      const float4 slo4 = *reinterpret_cast<const float4*>(sc + wm * T::WM + i * 32 + rl0);
+      const float4 shi4 = *reinterpret_cast<const float4*>(sc + T::BM + wm * T::WM + i * 32 + rl0);
+      const float slo[4] = {slo4.x, slo4.y, slo4.z, slo4.w};
+      const float shi[4] = {shi4.x, shi4.y, shi4.z, shi4.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+#pragma unroll
+        for (int j = 0; j < T::TJ; ++j) {
+          const int lo = acc_lo[i][j][4 * rq + e] >> 8;  // exact: both operands carried a factor 16
+          const int hi = acc_hi[i][j][4 * rq + e] >> 4;  // exact: the weights carried a factor 16
+          float t = __fmul_rn(static_cast<float>(lo), slo[e]);
+          t = __fmaf_rn(static_cast<float>(hi), shi[e], t);
+          const float y = __fmul_rn(t, sw[j]);
+          OutT* dst = reinterpret_cast<OutT*>(tb + (rl0 + e) * ROW) + j * 32 + (lane & 31);
+          if constexpr (ESZ == 2) *dst = bf16_rne(y);
+          else *dst = y;
+        }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int pass = 0; pass < 32 / ROWS_PER_PASS; ++pass) {
+      const int rl = pass * ROWS_PER_PASS + lane / CHUNKS, ch = lane % CHUNKS;
+      const int m = m0 + wm * T::WM + i * 32 + rl;
+      const int n = n0 + wn * T::WN + ch * PER16;
+      if (m < g.M && n < g.N) {
+        OutT* dst = yout + static_cast<int64_t>(m) * g.ldy + n;
+        if (vec_ok && n + PER16 <= g.N) {
+          *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(tb + rl * ROW + ch * 16);
+        } else {  // ragged right edge or unaligned rows: element by element, straight from LDS
+          const OutT* src = reinterpret_cast<const OutT*>(tb + rl * ROW + ch * 16);
+          for (int q = 0; q < PER16 && n + q < g.N; ++q) dst[q] = src[q];
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (g.acc_lo_dbg || g.acc_hi_dbg) {  // test hook: the exact accumulators, written element by element
+#pragma unroll
+    for (int i = 0; i < T::TI; ++i)
+#pragma unroll
+      for (int j = 0; j < T::TJ; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = m0 + wm * T::WM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          const int n = n0 + wn * T::WN + j * 32 + (lane & 31);
+          if (m < g.M && n < g.N) {
+            if (g.acc_lo_dbg) g.acc_lo_dbg[static_cast<int64_t>(m) * g.N + n] = acc_lo[i][j][r] >> 8;
+            if (g.acc_hi_dbg) g.acc_hi_dbg[static_cast<int64_t>(m) * g.N + n] = acc_hi[i][j][r] >> 4;
+          }
+        }
+  }
+}
+
+template <typename T>
+__device__ __forceinline__ void epilogue(const GemmArgs& g, char* lds, v16i (&acc_lo)[T::TI][T::TJ],
+                                         v16i (&acc_hi)[T::TI][T::TJ], int m0, int n0, int wm, int wn, int wave, int lane) {
+  if (g.out_bf16) epilogue_typed<T, uint16_t>(g, lds, acc_lo, acc_hi, m0, n0, wm, wn, wave, lane);
+  else epilogue_typed<T, float>(g, lds, acc_lo, acc_hi, m0, n0, wm, wn, wave, lane);
+}
+
 // MODE 0: dynamic (low + zero-padded high in one K loop); 1: static (low loop over K, then the
 // compact high loop over K_hi); 2: high loop only (plain W4A8 reference).
 template <typename T, int MODE>
@@ -265,33 +363,7 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmArgs g) {
     k_loop<T, false, true>(l2, lds, wm, wn, lane, acc_lo, acc_hi);
   }
 
-  // Epilogue: Y = (acc_lo * s_lo[m] + acc_hi * s_hi[m]) * s_w[n], in this order, in fp32.
-  // Accumulator register r of lane l of a 32x32 tile is row 8*(r/4) + 4*(l/32) + r%4, column l%32.
-#pragma unroll
-  for (int j = 0; j < T::TJ; ++j) {
-    const int n = n0 + wn * T::WN + j * 32 + (lane & 31);
-    const bool n_ok = n < g.N;
-    const float sw = n_ok ? g.s_w[n] : 0.0f;
-#pragma unroll
-    for (int i = 0; i < T::TI; ++i) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * T::WM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (n_ok && m < g.M) {
-          const int lo = acc_lo[i][j][r] >> 8;  // exact: both operands carried a factor 16
-          const int hi = acc_hi[i][j][r] >> 4;  // exact: the weights carried a factor 16
-          float t = g.s_lo ? __fmul_rn(static_cast<float>(lo), g.s_lo[m]) : 0.0f;
-          t = __fmaf_rn(static_cast<float>(hi), g.s_hi[m], t);
-          const float y = __fmul_rn(t, sw);
-          const int64_t o = static_cast<int64_t>(m) * g.ldy + n;
-          if (g.out_bf16) reinterpret_cast<uint16_t*>(g.y)[o] = bf16_rne(y);
-          else reinterpret_cast<float*>(g.y)[o] = y;
-          if (g.acc_lo_dbg) g.acc_lo_dbg[static_cast<int64_t>(m) * g.N + n] = lo;
-          if (g.acc_hi_dbg) g.acc_hi_dbg[static_cast<int64_t>(m) * g.N + n] = hi;
-        }
-      }
-    }
-  }
+  epilogue<T>(g, lds, acc_lo, acc_hi, m0, n0, wm, wn, wave, lane);
 }
 
 template <typename T, int MODE>
