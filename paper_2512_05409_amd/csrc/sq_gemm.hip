@@ -16,9 +16,9 @@
 //
 // Work split: a workgroup of 4 waves computes 128 tokens x 256 output channels; a wave computes
 // 64 tokens x 128 channels for BOTH products (2 x 2x4 tiles of 32x32, 256 accumulator registers).
-// A K step of 128 channels is staged through LDS, double buffered.  LDS rows are row-major with
-// the 16-byte chunk index XOR-swizzled by the row, which keeps both the staging stores (4 or 8
-// consecutive lanes per row) and the operand reads (32 consecutive rows per half wave) conflict-free.
+// A K step of 128 channels is copied into one of three LDS stages by LDS-direct loads, two steps
+// ahead of its use.  LDS rows are row-major with the 16-byte chunk index XOR-swizzled by the row,
+// which keeps the operand reads (32 consecutive rows per half wave) free of bank conflicts.
 #include "sq_device.h"
 
 namespace sq {
@@ -41,100 +41,135 @@ struct Tile {
   static constexpr int A_HI = BM * 64;        // [BM][128 B]  INT8
   static constexpr int B_OFF = A_HI + BM * 128;  // [BN][64 B] packed INT4
   static constexpr int STAGE = B_OFF + BN * 64;
-  static constexpr int LDS_BYTES = 2 * STAGE;
+  static constexpr int LDS_BYTES = 3 * STAGE;
 };
 
 // Byte offset of 16-byte chunk c of a row inside an operand tile.
 __device__ __forceinline__ int off4(int row, int c) { return (row << 6) + (((c ^ (row >> 2)) & 3) << 4); }   // 4 chunks / row
 __device__ __forceinline__ int off8(int row, int c) { return (row << 7) + (((c ^ (row >> 1)) & 7) << 4); }   // 8 chunks / row
 
-template <typename T>
-struct Staging {
-  v4u a_lo[T::BM * 4 / NT];
-  v4u a_hi[T::BM * 8 / NT];
-  v4u b[T::BN * 4 / NT];
-};
+// 16 zero bytes in device memory: the source of operand chunks that lie past the end of K.
+__device__ __attribute__((aligned(16))) const unsigned int kZeroChunk[4] = {0u, 0u, 0u, 0u};
 
-// Operand sources of one K loop.  LO: the packed low part is an operand; HI: an INT8 operand
-// (the zero-padded image of the high part, or the compact high codes) is.
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// s_waitcnt immediate (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14]):
+// at most n vector-memory operations (here: LDS-direct loads) outstanding, and no LDS operation.
+constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | (7 << 4) | (0 << 8) | ((n >> 4) << 14); }
+
+// Workgroup barrier for the K loop.  __syncthreads() would also wait for every outstanding
+// LDS-direct load (its release fence drains vmcnt), i.e. for the copy that was enqueued a moment
+// ago for two steps ahead.  Here the wave waits only until at most `pending` of its loads are in
+// flight (loads retire in order, so the older step is complete) and until its own LDS reads have
+// returned, then joins the barrier.  The empty asm statements stop the compiler from moving
+// memory accesses across it.
+template <int PENDING>
+__device__ __forceinline__ void pipeline_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(PENDING));
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// Operand sources of one K loop and the asynchronous copy of one K step into an LDS stage.
+// LO: the packed low part is an operand; HI: an INT8 operand (the zero-padded image of the high
+// part, or the compact high codes) is.  The copy uses LDS-direct loads (global_load_lds_dwordx4):
+// each wave instruction moves 64 x 16 bytes into 1 KB of LDS, lane l landing at byte 16*l, so the
+// XOR swizzle is applied on the global side: the lane that lands in position p of a row fetches
+// chunk p ^ swizzle(row).  Four (or eight) consecutive lanes still read 64 (128) contiguous bytes.
 template <typename T, bool LO, bool HI>
-struct Loader {
-  const uint8_t* a_lo;
-  int64_t lda_lo;
-  const int8_t* a_hi;
-  int64_t lda_hi;
-  const uint8_t* b;
-  int64_t ldb;
-  int kext;  // channels in this loop (multiple of 32)
-  int m0, n0, M, N;
+struct Pipe {
+  static constexpr int N_LO = LO ? T::BM * 4 / NT : 0;
+  static constexpr int N_HI = HI ? T::BM * 8 / NT : 0;
+  static constexpr int N_B = T::BN * 4 / NT;
+  static constexpr int NLOAD = N_LO + N_HI + N_B;  // loads per wave per K step
 
-  // Loads are unconditional from an address clamped into the operand: rows past the edge repeat the
-  // last row and are never stored; chunks past kext (only possible in the last, partial K step) read
-  // the last chunk and are zeroed when they are written to LDS.
-  __device__ __forceinline__ void load(Staging<T>& s, int k0) const {
+  const char* p_lo[N_LO > 0 ? N_LO : 1];  // per-lane source of each load at k = 0
+  const char* p_hi[N_HI > 0 ? N_HI : 1];
+  const char* p_b[N_B];
+  int kc_lo, kc_hi;  // first channel of this lane's chunk inside a K step (packed operands / INT8 operand)
+  int kext;          // channels in this loop (multiple of 32)
+  int wave;          // uniform
+
+  __device__ __forceinline__ void init(const uint8_t* a_lo, int64_t lda_lo, const int8_t* a_hi, int64_t lda_hi,
+                                       const uint8_t* b, int64_t ldb, int kext_, int m0, int n0, int M, int N) {
     const int tid = threadIdx.x;
-    if (LO) {
-#pragma unroll
-      for (int i = 0; i < T::BM * 4 / NT; ++i) {
-        const int idx = tid + NT * i, row = idx >> 2, c = idx & 3;
-        const int k = min(k0 + c * 32, kext - 32);
-        const int m = min(m0 + row, M - 1);
-        s.a_lo[i] = *reinterpret_cast<const v4u*>(a_lo + m * lda_lo + (k >> 1));
-      }
+    kext = kext_;
+    wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    {
+      const int row = tid >> 2;  // rows of later loads differ by a multiple of 64: same swizzle
+      kc_lo = (((tid & 3) ^ (row >> 2)) & 3) * 32;
     }
-    if (HI) {
-#pragma unroll
-      for (int i = 0; i < T::BM * 8 / NT; ++i) {
-        const int idx = tid + NT * i, row = idx >> 3, c = idx & 7;
-        const int k = min(k0 + c * 16, kext - 16);
-        const int m = min(m0 + row, M - 1);
-        s.a_hi[i] = *reinterpret_cast<const v4u*>(a_hi + m * lda_hi + k);
-      }
+    {
+      const int row = tid >> 3;  // rows of later loads differ by a multiple of 32
+      kc_hi = (((tid & 7) ^ (row >> 1)) & 7) * 16;
     }
 #pragma unroll
-    for (int i = 0; i < T::BN * 4 / NT; ++i) {
-      const int idx = tid + NT * i, row = idx >> 2, c = idx & 3;
-      const int k = min(k0 + c * 32, kext - 32);
-      const int n = min(n0 + row, N - 1);
-      s.b[i] = *reinterpret_cast<const v4u*>(b + n * ldb + (k >> 1));
+    for (int i = 0; i < N_LO; ++i) {
+      const int m = min(m0 + ((tid + NT * i) >> 2), M - 1);
+      p_lo[i] = reinterpret_cast<const char*>(a_lo) + m * lda_lo + (kc_lo >> 1);
+    }
+#pragma unroll
+    for (int i = 0; i < N_HI; ++i) {
+      const int m = min(m0 + ((tid + NT * i) >> 3), M - 1);
+      p_hi[i] = reinterpret_cast<const char*>(a_hi) + m * lda_hi + kc_hi;
+    }
+#pragma unroll
+    for (int i = 0; i < N_B; ++i) {
+      const int n = min(n0 + ((tid + NT * i) >> 2), N - 1);
+      p_b[i] = reinterpret_cast<const char*>(b) + n * ldb + (kc_lo >> 1);
     }
   }
 
-  __device__ __forceinline__ void store(Staging<T>& s, char* stage, int k0) const {
-    const int tid = threadIdx.x;
-    if (k0 + KS > kext) {  // partial K step (uniform branch): zero what lies past the end
-      const v4u zero = {0u, 0u, 0u, 0u};
+  // Enqueue the copy of K step `step` into `stage`.  Chunks past kext come from kZeroChunk.
+  __device__ __forceinline__ void issue(char* stage, int step) const {
+    const int k0 = step * KS;
+    const bool partial = k0 + KS > kext;  // uniform
+    const char* zero = reinterpret_cast<const char*>(kZeroChunk);
+    const bool lo_ok = !partial || (k0 + kc_lo < kext);
+    const bool hi_ok = !partial || (k0 + kc_hi < kext);
 #pragma unroll
-      for (int i = 0; i < T::BM * 4 / NT; ++i)
-        if (LO && k0 + ((tid + NT * i) & 3) * 32 >= kext) s.a_lo[i] = zero;
-#pragma unroll
-      for (int i = 0; i < T::BM * 8 / NT; ++i)
-        if (HI && k0 + ((tid + NT * i) & 7) * 16 >= kext) s.a_hi[i] = zero;
-#pragma unroll
-      for (int i = 0; i < T::BN * 4 / NT; ++i)
-        if (k0 + ((tid + NT * i) & 3) * 32 >= kext) s.b[i] = zero;
-    }
-    if (LO) {
-#pragma unroll
-      for (int i = 0; i < T::BM * 4 / NT; ++i) {
-        const int idx = tid + NT * i;
-        *reinterpret_cast<v4u*>(stage + T::A_LO + off4(idx >> 2, idx & 3)) = s.a_lo[i];
-      }
-    }
-    if (HI) {
-#pragma unroll
-      for (int i = 0; i < T::BM * 8 / NT; ++i) {
-        const int idx = tid + NT * i;
-        *reinterpret_cast<v4u*>(stage + T::A_HI + off8(idx >> 3, idx & 7)) = s.a_hi[i];
-      }
+    for (int i = 0; i < N_LO; ++i) {
+      const char* src = lo_ok ? p_lo[i] + (k0 >> 1) : zero;
+      __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(stage + T::A_LO + (NT * i + 64 * wave) * 16), 16, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < T::BN * 4 / NT; ++i) {
-      const int idx = tid + NT * i;
-      *reinterpret_cast<v4u*>(stage + T::B_OFF + off4(idx >> 2, idx & 3)) = s.b[i];
+    for (int i = 0; i < N_HI; ++i) {
+      const char* src = hi_ok ? p_hi[i] + k0 : zero;
+      __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(stage + T::A_HI + (NT * i + 64 * wave) * 16), 16, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < N_B; ++i) {
+      const char* src = lo_ok ? p_b[i] + (k0 >> 1) : zero;
+      __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(stage + T::B_OFF + (NT * i + 64 * wave) * 16), 16, 0, 0);
     }
   }
 };
+
+// The operands one wave needs for 64 channels (two matrix instructions deep) of its tile.
+template <typename T>
+struct Frags {
+  v4u alo[T::TI];     // packed low codes: 32 channels per row tile
+  v4u bw[T::TJ];      // packed weight codes
+  v4i ahi[T::TI][2];  // INT8 high codes, one 16-byte operand per matrix instruction
+};
+
+template <typename T, bool LO, bool HI>
+__device__ __forceinline__ void read_frags(Frags<T>& f, const char* stage, int g, int wm, int wn, int lane) {
+  const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < T::TJ; ++j)
+    f.bw[j] = *reinterpret_cast<const v4u*>(stage + T::B_OFF + off4(wn * T::WN + j * 32 + r, 2 * g + h));
+#pragma unroll
+  for (int i = 0; i < T::TI; ++i) {
+    const int row = wm * T::WM + i * 32 + r;
+    if (LO) f.alo[i] = *reinterpret_cast<const v4u*>(stage + T::A_LO + off4(row, 2 * g + h));
+    if (HI) {
+      f.ahi[i][0] = *reinterpret_cast<const v4i*>(stage + T::A_HI + off8(row, 4 * g + 2 * h));
+      f.ahi[i][1] = *reinterpret_cast<const v4i*>(stage + T::A_HI + off8(row, 4 * g + 2 * h + 1));
+    }
+  }
+}
 
 // One packed chunk (32 INT4 codes) -> the INT8 operands of two consecutive matrix instructions.
 __device__ __forceinline__ void widen(const v4u p, v4i& s0, v4i& s1) {
@@ -145,60 +180,92 @@ __device__ __forceinline__ void widen(const v4u p, v4i& s0, v4i& s1) {
 }
 
 template <typename T, bool LO, bool HI>
-__device__ __forceinline__ void compute_stage(const char* stage, int wm, int wn, int lane, v16i (&acc_lo)[T::TI][T::TJ],
-                                              v16i (&acc_hi)[T::TI][T::TJ]) {
-  const int r = lane & 31, h = lane >> 5;
+__device__ __forceinline__ void mma_frags(const Frags<T>& f, v16i (&acc_lo)[T::TI][T::TJ], v16i (&acc_hi)[T::TI][T::TJ]) {
+  v4i bw[T::TJ][2], alo[T::TI][2];
 #pragma unroll
-  for (int g = 0; g < KS / 64; ++g) {
-    v4i bw[T::TJ][2], alo[T::TI][2], ahi[T::TI][2];
+  for (int j = 0; j < T::TJ; ++j) widen(f.bw[j], bw[j][0], bw[j][1]);
+  if (LO) {
 #pragma unroll
-    for (int j = 0; j < T::TJ; ++j) {
-      const v4u p = *reinterpret_cast<const v4u*>(stage + T::B_OFF + off4(wn * T::WN + j * 32 + r, 2 * g + h));
-      widen(p, bw[j][0], bw[j][1]);
-    }
+    for (int i = 0; i < T::TI; ++i) widen(f.alo[i], alo[i][0], alo[i][1]);
+  }
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
 #pragma unroll
     for (int i = 0; i < T::TI; ++i) {
-      const int row = wm * T::WM + i * 32 + r;
-      if (LO) {
-        const v4u p = *reinterpret_cast<const v4u*>(stage + T::A_LO + off4(row, 2 * g + h));
-        widen(p, alo[i][0], alo[i][1]);
-      }
-      if (HI) {
-        ahi[i][0] = *reinterpret_cast<const v4i*>(stage + T::A_HI + off8(row, 4 * g + 2 * h));
-        ahi[i][1] = *reinterpret_cast<const v4i*>(stage + T::A_HI + off8(row, 4 * g + 2 * h + 1));
-      }
-    }
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-#pragma unroll
-      for (int i = 0; i < T::TI; ++i) {
-#pragma unroll
-        for (int j = 0; j < T::TJ; ++j) {
-          if (LO) acc_lo[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo[i][s], bw[j][s], acc_lo[i][j], 0, 0, 0);
-          if (HI) acc_hi[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi[i][s], bw[j][s], acc_hi[i][j], 0, 0, 0);
-        }
+      for (int j = 0; j < T::TJ; ++j) {
+        if (LO) acc_lo[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo[i][s], bw[j][s], acc_lo[i][j], 0, 0, 0);
+        if (HI) acc_hi[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.ahi[i][s], bw[j][s], acc_hi[i][j], 0, 0, 0);
       }
     }
   }
 }
 
+// K loop, three LDS stages.  In iteration kt the copy of step kt+2 is enqueued, the first half of
+// step kt is multiplied from registers while the second half is fetched from LDS, then every wave
+// waits for its own copy of step kt+1, the workgroup meets at a barrier, and the first half of
+// step kt+1 is fetched while the second half of step kt is multiplied: the matrix pipeline has
+// operands in registers on both sides of the barrier.
+// Safety: the stage overwritten by the copy of step kt+2 was last read (step kt-1) before the
+// barrier of iteration kt-1, and every wave drains its LDS reads (lgkmcnt 0) before that barrier.
+// One iteration of the K loop (see k_loop).  FILL: the copy of step kt+2 is enqueued; NEXT: step kt+1
+// exists and its first half is fetched after the barrier.
+template <typename T, bool LO, bool HI, bool FILL, bool NEXT>
+__device__ __forceinline__ void k_iteration(const Pipe<T, LO, HI>& pipe, char* lds, int kt, int st_cur, int wm, int wn,
+                                            int lane, Frags<T>& f0, Frags<T>& f1, v16i (&acc_lo)[T::TI][T::TJ],
+                                            v16i (&acc_hi)[T::TI][T::TJ]) {
+  constexpr int NL = Pipe<T, LO, HI>::NLOAD;
+  const int st_next = st_cur == 2 ? 0 : st_cur + 1;
+  const int st_fill = st_next == 2 ? 0 : st_next + 1;
+  // sched_barrier(0) pins the order "fetch the next operands, then multiply the current ones":
+  // left alone, the scheduler sinks the LDS reads next to their use to save registers and the
+  // matrix pipeline then waits for LDS several times per iteration.
+  if (FILL) pipe.issue(lds + st_fill * T::STAGE, kt + 2);
+  read_frags<T, LO, HI>(f1, lds + st_cur * T::STAGE, 1, wm, wn, lane);
+  __builtin_amdgcn_sched_barrier(0);
+  mma_frags<T, LO, HI>(f0, acc_lo, acc_hi);
+  __builtin_amdgcn_sched_barrier(0);
+  pipeline_barrier<FILL ? NL : 0>();
+  if (NEXT) read_frags<T, LO, HI>(f0, lds + st_next * T::STAGE, 0, wm, wn, lane);
+  __builtin_amdgcn_sched_barrier(0);
+  mma_frags<T, LO, HI>(f1, acc_lo, acc_hi);
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// K loop, three LDS stages.  In iteration kt the copy of step kt+2 is enqueued, the first half of
+// step kt is multiplied from registers while the second half is fetched from LDS, then every wave
+// waits for its own copy of step kt+1, the workgroup meets at a barrier, and the first half of
+// step kt+1 is fetched while the second half of step kt is multiplied: the matrix pipeline has
+// operands in registers on both sides of the barrier.  The last two iterations are peeled so that
+// the steady-state body has no branches.
+// Safety: the stage overwritten by the copy of step kt+2 was last read (step kt-1) before the
+// barrier of iteration kt-1, and every wave drains its LDS reads (lgkmcnt 0) before that barrier.
 template <typename T, bool LO, bool HI>
-__device__ __forceinline__ void k_loop(const Loader<T, LO, HI>& ld, char* lds, int wm, int wn, int lane,
+__device__ __forceinline__ void k_loop(const Pipe<T, LO, HI>& pipe, char* lds, int wm, int wn, int lane,
                                        v16i (&acc_lo)[T::TI][T::TJ], v16i (&acc_hi)[T::TI][T::TJ]) {
-  const int steps = (ld.kext + KS - 1) / KS;
-  Staging<T> s;
-  ld.load(s, 0);
-  ld.store(s, lds, 0);
-  __syncthreads();
-  for (int kt = 0; kt < steps; ++kt) {
-    char* cur = lds + (kt & 1) * T::STAGE;
-    char* nxt = lds + ((kt + 1) & 1) * T::STAGE;
-    const bool more = (kt + 1) < steps;
-    if (more) ld.load(s, (kt + 1) * KS);
-    compute_stage<T, LO, HI>(cur, wm, wn, lane, acc_lo, acc_hi);
-    if (more) ld.store(s, nxt, (kt + 1) * KS);
-    __syncthreads();
+  constexpr int NL = Pipe<T, LO, HI>::NLOAD;
+  const int steps = (pipe.kext + KS - 1) / KS;
+  pipe.issue(lds, 0);
+  if (steps > 1) {
+    pipe.issue(lds + T::STAGE, 1);
+    pipeline_barrier<NL>();
+  } else {
+    pipeline_barrier<0>();
   }
+  Frags<T> f0, f1;
+  read_frags<T, LO, HI>(f0, lds, 0, wm, wn, lane);
+  int st = 0, kt = 0;
+  for (; kt + 2 < steps; ++kt) {
+    k_iteration<T, LO, HI, true, true>(pipe, lds, kt, st, wm, wn, lane, f0, f1, acc_lo, acc_hi);
+    st = st == 2 ? 0 : st + 1;
+  }
+  if (kt + 1 < steps) {
+    k_iteration<T, LO, HI, false, true>(pipe, lds, kt, st, wm, wn, lane, f0, f1, acc_lo, acc_hi);
+    st = st == 2 ? 0 : st + 1;
+    ++kt;
+  }
+  k_iteration<T, LO, HI, false, false>(pipe, lds, kt, st, wm, wn, lane, f0, f1, acc_lo, acc_hi);
+  __syncthreads();  // the stages are reused by the next loop / the epilogue
 }
 
 __device__ __forceinline__ uint16_t bf16_rne(float f) {
@@ -351,16 +418,18 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmArgs g) {
       }
 
   if (MODE == 0) {
-    Loader<T, true, true> ld{g.a_lo, g.K / 2, g.a_hi_dense, g.K, g.wq, g.K / 2, g.K, m0, n0, g.M, g.N};
-    k_loop<T, true, true>(ld, lds, wm, wn, lane, acc_lo, acc_hi);
-  } else if (MODE == 1) {
-    Loader<T, true, false> l1{g.a_lo, g.K / 2, nullptr, 0, g.wq, g.K / 2, g.K, m0, n0, g.M, g.N};
-    k_loop<T, true, false>(l1, lds, wm, wn, lane, acc_lo, acc_hi);
-    Loader<T, false, true> l2{nullptr, 0, g.a_hi_compact, g.lda_hi_compact, g.w_hi, g.K_hi / 2, g.K_hi, m0, n0, g.M, g.N};
-    k_loop<T, false, true>(l2, lds, wm, wn, lane, acc_lo, acc_hi);
+    Pipe<T, true, true> pipe;
+    pipe.init(g.a_lo, g.K / 2, g.a_hi_dense, g.K, g.wq, g.K / 2, g.K, m0, n0, g.M, g.N);
+    k_loop<T, true, true>(pipe, lds, wm, wn, lane, acc_lo, acc_hi);
   } else {
-    Loader<T, false, true> l2{nullptr, 0, g.a_hi_compact, g.lda_hi_compact, g.w_hi, g.K_hi / 2, g.K_hi, m0, n0, g.M, g.N};
-    k_loop<T, false, true>(l2, lds, wm, wn, lane, acc_lo, acc_hi);
+    if (MODE == 1) {
+      Pipe<T, true, false> p1;
+      p1.init(g.a_lo, g.K / 2, nullptr, 0, g.wq, g.K / 2, g.K, m0, n0, g.M, g.N);
+      k_loop<T, true, false>(p1, lds, wm, wn, lane, acc_lo, acc_hi);
+    }
+    Pipe<T, false, true> p2;
+    p2.init(nullptr, 0, g.a_hi_compact, g.lda_hi_compact, g.w_hi, g.K_hi / 2, g.K_hi, m0, n0, g.M, g.N);
+    k_loop<T, false, true>(p2, lds, wm, wn, lane, acc_lo, acc_hi);
   }
 
   epilogue<T>(g, lds, acc_lo, acc_hi, m0, n0, wm, wn, wave, lane);
