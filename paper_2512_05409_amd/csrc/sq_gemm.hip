@@ -171,73 +171,110 @@ __device__ __forceinline__ void read_frags(Frags<T>& f, const char* stage, int g
   }
 }
 
-// One packed chunk (32 INT4 codes) -> the INT8 operands of two consecutive matrix instructions.
-__device__ __forceinline__ void widen(const v4u p, v4i& s0, v4i& s1) {
-  const v4u e = (p << 4) & 0xF0F0F0F0u;
-  const v4u o = p & 0xF0F0F0F0u;
-  s0 = v4i{static_cast<int>(e[0]), static_cast<int>(o[0]), static_cast<int>(e[1]), static_cast<int>(o[1])};
-  s1 = v4i{static_cast<int>(e[2]), static_cast<int>(o[2]), static_cast<int>(e[3]), static_cast<int>(o[3])};
+// Half s (0/1) of a packed chunk (16 of its 32 INT4 codes) -> the INT8 operand of matrix instruction s.
+__device__ __forceinline__ v4i widen(const v4u p, int s) {
+  const unsigned a = p[2 * s], b = p[2 * s + 1];
+  return v4i{static_cast<int>((a << 4) & 0xF0F0F0F0u), static_cast<int>(a & 0xF0F0F0F0u),
+             static_cast<int>((b << 4) & 0xF0F0F0F0u), static_cast<int>(b & 0xF0F0F0F0u)};
 }
 
-template <typename T, bool LO, bool HI>
-__device__ __forceinline__ void mma_frags(const Frags<T>& f, v16i (&acc_lo)[T::TI][T::TJ], v16i (&acc_hi)[T::TI][T::TJ]) {
-  v4i bw[T::TJ][2], alo[T::TI][2];
+// Widened operands of one 32-channel slice of the fragments.
+template <typename T>
+struct Wide {
+  v4i bw[T::TJ];
+  v4i alo[T::TI];
+};
+
+template <typename T, bool LO>
+__device__ __forceinline__ void widen_slice(Wide<T>& w, const Frags<T>& f, int s) {
 #pragma unroll
-  for (int j = 0; j < T::TJ; ++j) widen(f.bw[j], bw[j][0], bw[j][1]);
+  for (int j = 0; j < T::TJ; ++j) w.bw[j] = widen(f.bw[j], s);
   if (LO) {
 #pragma unroll
-    for (int i = 0; i < T::TI; ++i) widen(f.alo[i], alo[i][0], alo[i][1]);
+    for (int i = 0; i < T::TI; ++i) w.alo[i] = widen(f.alo[i], s);
   }
+}
+
+// The matrix instructions of one 32-channel slice (s = 0/1): 2 * TI * TJ of them, all independent.
+template <typename T, bool LO, bool HI>
+__device__ __forceinline__ void mma_slice(const Wide<T>& w, const Frags<T>& f, int s, v16i (&acc_lo)[T::TI][T::TJ],
+                                          v16i (&acc_hi)[T::TI][T::TJ]) {
 #pragma unroll
-  for (int s = 0; s < 2; ++s) {
+  for (int i = 0; i < T::TI; ++i) {
 #pragma unroll
-    for (int i = 0; i < T::TI; ++i) {
-#pragma unroll
-      for (int j = 0; j < T::TJ; ++j) {
-        if (LO) acc_lo[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo[i][s], bw[j][s], acc_lo[i][j], 0, 0, 0);
-        if (HI) acc_hi[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.ahi[i][s], bw[j][s], acc_hi[i][j], 0, 0, 0);
-      }
+    for (int j = 0; j < T::TJ; ++j) {
+      if (LO) acc_lo[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w.alo[i], w.bw[j], acc_lo[i][j], 0, 0, 0);
+      if (HI) acc_hi[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.ahi[i][s], w.bw[j], acc_hi[i][j], 0, 0, 0);
     }
   }
 }
 
-// K loop, three LDS stages.  In iteration kt the copy of step kt+2 is enqueued, the first half of
-// step kt is multiplied from registers while the second half is fetched from LDS, then every wave
-// waits for its own copy of step kt+1, the workgroup meets at a barrier, and the first half of
-// step kt+1 is fetched while the second half of step kt is multiplied: the matrix pipeline has
-// operands in registers on both sides of the barrier.
-// Safety: the stage overwritten by the copy of step kt+2 was last read (step kt-1) before the
-// barrier of iteration kt-1, and every wave drains its LDS reads (lgkmcnt 0) before that barrier.
-// One iteration of the K loop (see k_loop).  FILL: the copy of step kt+2 is enqueued; NEXT: step kt+1
-// exists and its first half is fetched after the barrier.
+// Scheduling recipe for one slice: every matrix instruction is followed by a few of the other
+// instructions of the region (a wave issues in order, so whatever is not tucked behind a matrix
+// instruction leaves the matrix pipeline idle).  VMEM / DS: how many of the first slots also take
+// one LDS-direct load / one LDS read.
+template <int NMFMA, int VALU, int SALU, int VMEM, int DS>
+__device__ __forceinline__ void interleave() {
+#pragma unroll
+  for (int k = 0; k < NMFMA; ++k) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if (VALU) __builtin_amdgcn_sched_group_barrier(0x002, VALU, 0);
+    if (SALU) __builtin_amdgcn_sched_group_barrier(0x004, SALU, 0);
+    if (k < VMEM) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    if (k < DS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+  }
+}
+
+// One iteration of the K loop (see k_loop): four slices of 32 channels.  While the matrix
+// instructions of a slice run, the operands of the following slice are widened, and the packed
+// operands of the slice after that are fetched from LDS, so nothing a matrix instruction needs was
+// requested less than a slice (about 500 cycles) earlier.
+//   on entry: f0 = fragments of (step kt, channels 0-63), w0 = its slice 0, widened
+//   slice A: multiply w0     | fetch f1 = (step kt, channels 64-127), widen f0 slice 1 -> w1
+//   slice B: multiply w1     | enqueue the copy of step kt+2, widen f1 slice 0 -> w0
+//   barrier (step kt+1 is complete in LDS, step kt's stage may be overwritten)
+//   slice C: multiply w0     | fetch f0 = (step kt+1, channels 0-63), widen f1 slice 1 -> w1
+//   slice D: multiply w1     | widen f0 slice 0 -> w0
+// FILL: the copy of step kt+2 is enqueued; NEXT: step kt+1 exists.
 template <typename T, bool LO, bool HI, bool FILL, bool NEXT>
 __device__ __forceinline__ void k_iteration(const Pipe<T, LO, HI>& pipe, char* lds, int kt, int st_cur, int wm, int wn,
-                                            int lane, Frags<T>& f0, Frags<T>& f1, v16i (&acc_lo)[T::TI][T::TJ],
-                                            v16i (&acc_hi)[T::TI][T::TJ]) {
+                                            int lane, Frags<T>& f0, Frags<T>& f1, Wide<T>& w0, Wide<T>& w1,
+                                            v16i (&acc_lo)[T::TI][T::TJ], v16i (&acc_hi)[T::TI][T::TJ]) {
   constexpr int NL = Pipe<T, LO, HI>::NLOAD;
+  constexpr int NM = (LO ? 1 : 0) * T::TI * T::TJ + (HI ? 1 : 0) * T::TI * T::TJ;  // matrix instructions per slice
+  constexpr int NR = T::TJ + (LO ? T::TI : 0) + (HI ? 2 * T::TI : 0);               // LDS reads per fragment set
   const int st_next = st_cur == 2 ? 0 : st_cur + 1;
   const int st_fill = st_next == 2 ? 0 : st_next + 1;
-  // sched_barrier(0) pins the order "fetch the next operands, then multiply the current ones":
-  // left alone, the scheduler sinks the LDS reads next to their use to save registers and the
-  // matrix pipeline then waits for LDS several times per iteration.
-  if (FILL) pipe.issue(lds + st_fill * T::STAGE, kt + 2);
+  // slice A
   read_frags<T, LO, HI>(f1, lds + st_cur * T::STAGE, 1, wm, wn, lane);
+  widen_slice<T, LO>(w1, f0, 1);
+  mma_slice<T, LO, HI>(w0, f0, 0, acc_lo, acc_hi);
+  interleave<NM, 4, 0, 0, NR>();
   __builtin_amdgcn_sched_barrier(0);
-  mma_frags<T, LO, HI>(f0, acc_lo, acc_hi);
+  // slice B
+  if (FILL) pipe.issue(lds + st_fill * T::STAGE, kt + 2);
+  widen_slice<T, LO>(w0, f1, 0);
+  mma_slice<T, LO, HI>(w1, f0, 1, acc_lo, acc_hi);
+  interleave<NM, 6, 3, FILL ? NL : 0, 0>();
   __builtin_amdgcn_sched_barrier(0);
   pipeline_barrier<FILL ? NL : 0>();
+  // slice C
   if (NEXT) read_frags<T, LO, HI>(f0, lds + st_next * T::STAGE, 0, wm, wn, lane);
+  widen_slice<T, LO>(w1, f1, 1);
+  mma_slice<T, LO, HI>(w0, f1, 0, acc_lo, acc_hi);
+  interleave<NM, 4, 0, 0, NEXT ? NR : 0>();
   __builtin_amdgcn_sched_barrier(0);
-  mma_frags<T, LO, HI>(f1, acc_lo, acc_hi);
+  // slice D
+  if (NEXT) widen_slice<T, LO>(w0, f0, 0);
+  mma_slice<T, LO, HI>(w1, f1, 1, acc_lo, acc_hi);
+  interleave<NM, 3, 0, 0, 0>();
   __builtin_amdgcn_sched_barrier(0);
 }
 
-// K loop, three LDS stages.  In iteration kt the copy of step kt+2 is enqueued, the first half of
-// step kt is multiplied from registers while the second half is fetched from LDS, then every wave
-// waits for its own copy of step kt+1, the workgroup meets at a barrier, and the first half of
-// step kt+1 is fetched while the second half of step kt is multiplied: the matrix pipeline has
-// operands in registers on both sides of the barrier.  The last two iterations are peeled so that
-// the steady-state body has no branches.
+// K loop, three LDS stages: the copy of step kt+2 is enqueued while step kt is multiplied; every wave
+// waits for its own copy of step kt+1 in the middle of iteration kt, the workgroup meets at a barrier,
+// and the matrix pipeline has operands in registers on both sides of it (see k_iteration).  The last
+// two iterations are peeled so that the steady-state body has no branches.
 // Safety: the stage overwritten by the copy of step kt+2 was last read (step kt-1) before the
 // barrier of iteration kt-1, and every wave drains its LDS reads (lgkmcnt 0) before that barrier.
 template <typename T, bool LO, bool HI>
@@ -253,18 +290,20 @@ __device__ __forceinline__ void k_loop(const Pipe<T, LO, HI>& pipe, char* lds, i
     pipeline_barrier<0>();
   }
   Frags<T> f0, f1;
+  Wide<T> w0, w1;
   read_frags<T, LO, HI>(f0, lds, 0, wm, wn, lane);
+  widen_slice<T, LO>(w0, f0, 0);
   int st = 0, kt = 0;
   for (; kt + 2 < steps; ++kt) {
-    k_iteration<T, LO, HI, true, true>(pipe, lds, kt, st, wm, wn, lane, f0, f1, acc_lo, acc_hi);
+    k_iteration<T, LO, HI, true, true>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
     st = st == 2 ? 0 : st + 1;
   }
   if (kt + 1 < steps) {
-    k_iteration<T, LO, HI, false, true>(pipe, lds, kt, st, wm, wn, lane, f0, f1, acc_lo, acc_hi);
+    k_iteration<T, LO, HI, false, true>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
     st = st == 2 ? 0 : st + 1;
     ++kt;
   }
-  k_iteration<T, LO, HI, false, false>(pipe, lds, kt, st, wm, wn, lane, f0, f1, acc_lo, acc_hi);
+  k_iteration<T, LO, HI, false, false>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
   __syncthreads();  // the stages are reused by the next loop / the epilogue
 }
 
