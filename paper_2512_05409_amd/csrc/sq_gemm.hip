@@ -121,13 +121,14 @@ struct Pipe {
     }
   }
 
-  // Enqueue the copy of K step `step` into `stage`.  Chunks past kext come from kZeroChunk.
+  // Enqueue the copy of K step `step` into `stage`.  TAIL: the step may reach past kext (only the last
+  // step of a loop can); its chunks past the end come from kZeroChunk.
+  template <bool TAIL>
   __device__ __forceinline__ void issue(char* stage, int step) const {
     const int k0 = step * KS;
-    const bool partial = k0 + KS > kext;  // uniform
     const char* zero = reinterpret_cast<const char*>(kZeroChunk);
-    const bool lo_ok = !partial || (k0 + kc_lo < kext);
-    const bool hi_ok = !partial || (k0 + kc_hi < kext);
+    const bool lo_ok = !TAIL || (k0 + kc_lo < kext);
+    const bool hi_ok = !TAIL || (k0 + kc_hi < kext);
 #pragma unroll
     for (int i = 0; i < N_LO; ++i) {
       const char* src = lo_ok ? p_lo[i] + (k0 >> 1) : zero;
@@ -235,8 +236,9 @@ __device__ __forceinline__ void interleave() {
 //   barrier (step kt+1 is complete in LDS, step kt's stage may be overwritten)
 //   slice C: multiply w0     | fetch f0 = (step kt+1, channels 0-63), widen f1 slice 1 -> w1
 //   slice D: multiply w1     | widen f0 slice 0 -> w0
-// FILL: the copy of step kt+2 is enqueued; NEXT: step kt+1 exists.
-template <typename T, bool LO, bool HI, bool FILL, bool NEXT>
+// FILL: 0 = nothing to copy, 1 = the copy of step kt+2 is enqueued, 2 = the same and that step may be
+// partial; NEXT: step kt+1 exists.
+template <typename T, bool LO, bool HI, int FILL, bool NEXT>
 __device__ __forceinline__ void k_iteration(const Pipe<T, LO, HI>& pipe, char* lds, int kt, int st_cur, int wm, int wn,
                                             int lane, Frags<T>& f0, Frags<T>& f1, Wide<T>& w0, Wide<T>& w1,
                                             v16i (&acc_lo)[T::TI][T::TJ], v16i (&acc_hi)[T::TI][T::TJ]) {
@@ -252,7 +254,8 @@ __device__ __forceinline__ void k_iteration(const Pipe<T, LO, HI>& pipe, char* l
   interleave<NM, 4, 0, 0, NR>();
   __builtin_amdgcn_sched_barrier(0);
   // slice B
-  if (FILL) pipe.issue(lds + st_fill * T::STAGE, kt + 2);
+  if (FILL == 1) pipe.template issue<false>(lds + st_fill * T::STAGE, kt + 2);
+  if (FILL == 2) pipe.template issue<true>(lds + st_fill * T::STAGE, kt + 2);
   widen_slice<T, LO>(w0, f1, 0);
   mma_slice<T, LO, HI>(w1, f0, 1, acc_lo, acc_hi);
   interleave<NM, 6, 3, FILL ? NL : 0, 0>();
@@ -282,9 +285,9 @@ __device__ __forceinline__ void k_loop(const Pipe<T, LO, HI>& pipe, char* lds, i
                                        v16i (&acc_lo)[T::TI][T::TJ], v16i (&acc_hi)[T::TI][T::TJ]) {
   constexpr int NL = Pipe<T, LO, HI>::NLOAD;
   const int steps = (pipe.kext + KS - 1) / KS;
-  pipe.issue(lds, 0);
+  pipe.template issue<true>(lds, 0);
   if (steps > 1) {
-    pipe.issue(lds + T::STAGE, 1);
+    pipe.template issue<true>(lds + T::STAGE, 1);
     pipeline_barrier<NL>();
   } else {
     pipeline_barrier<0>();
@@ -294,23 +297,33 @@ __device__ __forceinline__ void k_loop(const Pipe<T, LO, HI>& pipe, char* lds, i
   read_frags<T, LO, HI>(f0, lds, 0, wm, wn, lane);
   widen_slice<T, LO>(w0, f0, 0);
   int st = 0, kt = 0;
-  for (; kt + 2 < steps; ++kt) {
-    k_iteration<T, LO, HI, true, true>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
+  for (; kt + 3 < steps; ++kt) {  // copies of full steps only
+    k_iteration<T, LO, HI, 1, true>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
     st = st == 2 ? 0 : st + 1;
   }
-  if (kt + 1 < steps) {
-    k_iteration<T, LO, HI, false, true>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
+  if (kt + 2 < steps) {  // enqueues the last step, which may be partial
+    k_iteration<T, LO, HI, 2, true>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
     st = st == 2 ? 0 : st + 1;
     ++kt;
   }
-  k_iteration<T, LO, HI, false, false>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
+  if (kt + 1 < steps) {
+    k_iteration<T, LO, HI, 0, true>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
+    st = st == 2 ? 0 : st + 1;
+    ++kt;
+  }
+  k_iteration<T, LO, HI, 0, false>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
   __syncthreads();  // the stages are reused by the next loop / the epilogue
 }
 
-__device__ __forceinline__ uint16_t bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return static_cast<uint16_t>(u >> 16);
+// fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint16_t bf16_rne(float f) { return __builtin_bit_cast(uint16_t, static_cast<__bf16>(f)); }
+
+// Orders this wave's LDS writes before its later LDS reads of other lanes' data (compiler barrier +
+// wait for the wave's outstanding LDS operations); no other wave is involved.
+__device__ __forceinline__ void wave_lds_fence() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt((15) | (7 << 4) | (0 << 8) | (3 << 14));  // lgkmcnt(0)
+  asm volatile("" ::: "memory");
 }
 
 // Maps the linear workgroup id to a tile so that (a) the workgroups resident on one XCD at a time
@@ -353,9 +366,11 @@ __device__ __forceinline__ void epilogue_typed(const GemmArgs& g, char* lds, v16
   float* sc = reinterpret_cast<float*>(lds);  // [0, BM): s_lo, [BM, 2 BM): s_hi   (BM <= 128)
   char* tb = lds + 1024 + wave * (32 * ROW);
   if (tid < T::BM) {
+    // The accumulators still carry the widening factors (256 and 16); folding the inverse powers of two
+    // into the scales is exact and leaves every rounding of the epilogue where it was.
     const int m = min(m0 + tid, g.M - 1);
-    sc[tid] = g.s_lo ? g.s_lo[m] : 0.0f;
-    sc[T::BM + tid] = g.s_hi[m];
+    sc[tid] = g.s_lo ? g.s_lo[m] * (1.0f / 256.0f) : 0.0f;
+    sc[T::BM + tid] = g.s_hi[m] * (1.0f / 16.0f);
   }
   __syncthreads();
   float sw[T::TJ];
@@ -379,10 +394,8 @@ __device__ __forceinline__ void epilogue_typed(const GemmArgs& g, char* lds, v16
       for (int e = 0; e < 4; ++e) {
 #pragma unroll
         for (int j = 0; j < T::TJ; ++j) {
-          const int lo = acc_lo[i][j][4 * rq + e] >> 8;  // exact: both operands carried a factor 16
-          const int hi = acc_hi[i][j][4 * rq + e] >> 4;  // exact: the weights carried a factor 16
-          float t = __fmul_rn(static_cast<float>(lo), slo[e]);
-          t = __fmaf_rn(static_cast<float>(hi), shi[e], t);
+          float t = __fmul_rn(static_cast<float>(acc_lo[i][j][4 * rq + e]), slo[e]);
+          t = __fmaf_rn(static_cast<float>(acc_hi[i][j][4 * rq + e]), shi[e], t);
           const float y = __fmul_rn(t, sw[j]);
           OutT* dst = reinterpret_cast<OutT*>(tb + (rl0 + e) * ROW) + j * 32 + (lane & 31);
           if constexpr (ESZ == 2) *dst = bf16_rne(y);
@@ -390,7 +403,7 @@ __device__ __forceinline__ void epilogue_typed(const GemmArgs& g, char* lds, v16
         }
       }
     }
-    __syncthreads();
+    wave_lds_fence();  // the buffer is private to the wave: its LDS operations execute in order
 #pragma unroll
     for (int pass = 0; pass < 32 / ROWS_PER_PASS; ++pass) {
       const int rl = pass * ROWS_PER_PASS + lane / CHUNKS, ch = lane % CHUNKS;
@@ -406,7 +419,7 @@ __device__ __forceinline__ void epilogue_typed(const GemmArgs& g, char* lds, v16
         }
       }
     }
-    __syncthreads();
+    wave_lds_fence();
   }
   if (g.acc_lo_dbg || g.acc_hi_dbg) {  // test hook: the exact accumulators, written element by element
 #pragma unroll
