@@ -44,7 +44,9 @@ def parse():
     ap.add_argument("--topk", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the CPU-oracle sample (0: sized for about 15 s)")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the CPU-oracle sample (0: sized for about 20 s)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain device copy of 256 MiB (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -74,7 +76,7 @@ def cpu_baseline(wl, mask, rows_req):
     if rows_req > 0:
         n = min(wl.M, rows_req)
     else:
-        n = int(min(wl.M, max(len(probe_rows), len(probe_rows) * 15.0 / max(t_probe, 1e-3))))
+        n = int(min(wl.M, max(len(probe_rows), len(probe_rows) * 20.0 / max(t_probe, 1e-3))))
         n = max(cores, (n // cores) * cores)
     rows = np.linspace(0, wl.M - 1, num=n, dtype=np.int64)
     xs = np.ascontiguousarray(wl.x_bits[rows])
@@ -156,6 +158,15 @@ def main():
         sq.sq_gemm(p, a, w, ys[i % n_y], None)
         if ev is not None:
             ev[2].record()
+
+    if args.copy_calibration:
+        # A copy kernel of known size: reads 2^28 bytes and writes 2^28 bytes per launch.
+        src = torch.ones(1 << 28, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         step(i)
