@@ -506,13 +506,220 @@ int launch_mode(const GemmArgs& g, hipStream_t st) {
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Decode shapes (M <= 64, dynamic mode): the layer is bound by streaming the INT4 weights once from
+// HBM, not by the matrix cores, and HBM needs tens of kilobytes in flight per compute unit.
+// Vector-memory operations of a wave retire in order, so one wave cannot keep a deep queue of weight
+// loads and, at the same time, wait for the shallow queue of (L2-resident) activation loads.  The
+// workgroup is therefore specialised: waves 0 and 1 multiply (32 output channels each, all tokens)
+// and copy the activation tiles two K steps ahead; wave 2 only copies weights, seven K steps ahead,
+// into its own ring of eight LDS stages.  Each wave waits on its own counter; one workgroup barrier
+// per K step publishes both copies.  A workgroup covers 64 output channels, so N/64 workgroups
+// (two or three per compute unit) stream disjoint weight rows.
+// TI = number of 32-token blocks (1: M <= 32, 2: M <= 64).  Requires K % 128 == 0.
+template <int TI>
+struct SkinnyCfg {
+  static constexpr int BM = 32 * TI;
+  static constexpr int BN = 64;
+  static constexpr int A_LO = 0;
+  static constexpr int A_HI = BM * 64;
+  static constexpr int A_STAGE = BM * 192;
+  static constexpr int A_STAGES = 3;
+  static constexpr int W_OFF = A_STAGES * A_STAGE;
+  static constexpr int W_STAGE = BN * 64;
+  static constexpr int W_STAGES = 8;
+  static constexpr int W_AHEAD = W_STAGES - 1;
+  static constexpr int LDS_BYTES = W_OFF + W_STAGES * W_STAGE;
+  static constexpr int N_LO = BM * 4 / 128;   // activation copies per consumer wave and K step
+  static constexpr int N_HI = BM * 8 / 128;
+  static constexpr int NA = N_LO + N_HI;
+  static constexpr int THREADS = 192;
+};
+
+// Weight loader wave: the four wave copies (64 rows x 64 bytes) of K step `step` into its ring stage.
+template <int TI>
+__device__ __forceinline__ void skinny_issue_w(const char* const (&src)[4], char* lds, int step) {
+  typedef SkinnyCfg<TI> C;
+  char* dst = lds + C::W_OFF + (step % C::W_STAGES) * C::W_STAGE;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    __builtin_amdgcn_global_load_lds(src[q] + step * 64, (lds_ptr_t)(dst + q * 1024), 16, 0, 0);
+}
+
+// Consumer waves: this wave's share of the activation tiles of K step `step`.
+template <int TI>
+__device__ __forceinline__ void skinny_issue_a(const char* const (&p_lo)[SkinnyCfg<TI>::N_LO],
+                                               const char* const (&p_hi)[SkinnyCfg<TI>::N_HI], char* lds, int step,
+                                               int wave) {
+  typedef SkinnyCfg<TI> C;
+  char* dst = lds + (step % C::A_STAGES) * C::A_STAGE;
+#pragma unroll
+  for (int i = 0; i < C::N_LO; ++i)
+    __builtin_amdgcn_global_load_lds(p_lo[i] + step * 64, (lds_ptr_t)(dst + C::A_LO + (128 * i + 64 * wave) * 16), 16, 0, 0);
+#pragma unroll
+  for (int i = 0; i < C::N_HI; ++i)
+    __builtin_amdgcn_global_load_lds(p_hi[i] + step * 128, (lds_ptr_t)(dst + C::A_HI + (128 * i + 64 * wave) * 16), 16, 0, 0);
+}
+
+template <int TI>
+__global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
+  typedef SkinnyCfg<TI> C;
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n0 = blockIdx.x * C::BN;
+  const int steps = g.K / KS;
+  constexpr int W_AHEAD = C::W_AHEAD;
+
+  if (wave == 2) {
+    // ---- weight loader: 4 wave copies (64 rows x 64 bytes) per K step, W_AHEAD steps ahead ----
+    const char* src[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int row = 16 * q + (lane >> 2);
+      const int c = ((lane & 3) ^ (row >> 2)) & 3;
+      src[q] = reinterpret_cast<const char*>(g.wq) + static_cast<int64_t>(min(n0 + row, g.N - 1)) * (g.K / 2) + c * 16;
+    }
+    const int pre = min(C::W_AHEAD, steps);
+    for (int s2 = 0; s2 < pre; ++s2) skinny_issue_w<TI>(src, lds, s2);
+    if (pre == C::W_AHEAD) pipeline_barrier<4 * (C::W_AHEAD - 1)>();  // step 0 has landed
+    else pipeline_barrier<0>();
+    for (int kt = 0; kt < steps; ++kt) {
+      if (kt + C::W_AHEAD < steps) {
+        const int ahead = kt + W_AHEAD;
+        skinny_issue_w<TI>(src, lds, ahead);
+        pipeline_barrier<4 * (C::W_AHEAD - 1)>();  // step kt+1 has landed, six younger steps stay in flight
+      } else {
+        pipeline_barrier<0>();
+      }
+    }
+    return;
+  }
+
+  // ---- consumers ----
+  const int r = lane & 31, h = lane >> 5;
+  const char* p_lo[C::N_LO];
+  const char* p_hi[C::N_HI];
+#pragma unroll
+  for (int i = 0; i < C::N_LO; ++i) {
+    const int idx = tid + 128 * i, row = idx >> 2;
+    const int c = ((idx & 3) ^ (row >> 2)) & 3;
+    p_lo[i] = reinterpret_cast<const char*>(g.a_lo) + static_cast<int64_t>(min(row, g.M - 1)) * (g.K / 2) + c * 16;
+  }
+#pragma unroll
+  for (int i = 0; i < C::N_HI; ++i) {
+    const int idx = tid + 128 * i, row = idx >> 3;
+    const int c = ((idx & 7) ^ (row >> 1)) & 7;
+    p_hi[i] = reinterpret_cast<const char*>(g.a_hi_dense) + static_cast<int64_t>(min(row, g.M - 1)) * g.K + c * 16;
+  }
+
+  // per-token scales of the rows this lane's accumulator registers hold, with the widening factors folded in
+  float slo[TI][16], shi[TI][16];
+#pragma unroll
+  for (int i = 0; i < TI; ++i)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int m = min(i * 32 + 8 * (q >> 2) + 4 * h + (q & 3), g.M - 1);
+      slo[i][q] = g.s_lo[m] * (1.0f / 256.0f);
+      shi[i][q] = g.s_hi[m] * (1.0f / 16.0f);
+    }
+  const int n = n0 + wave * 32 + r;
+  const float sw = g.s_w[min(n, g.N - 1)];
+
+  v16i acc_lo[TI], acc_hi[TI];
+#pragma unroll
+  for (int i = 0; i < TI; ++i)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      acc_lo[i][q] = 0;
+      acc_hi[i][q] = 0;
+    }
+
+  skinny_issue_a<TI>(p_lo, p_hi, lds, 0, wave);
+  if (steps > 1) {
+    skinny_issue_a<TI>(p_lo, p_hi, lds, 1, wave);
+    pipeline_barrier<C::NA>();
+  } else {
+    pipeline_barrier<0>();
+  }
+  for (int kt = 0; kt < steps; ++kt) {
+    const bool fill = kt + 2 < steps;
+    if (fill) skinny_issue_a<TI>(p_lo, p_hi, lds, kt + 2, wave);
+    const char* sa = lds + (kt % C::A_STAGES) * C::A_STAGE;
+    const char* sw_stage = lds + C::W_OFF + (kt % C::W_STAGES) * C::W_STAGE;
+#pragma unroll
+    for (int gq = 0; gq < 2; ++gq) {
+      const v4u wp = *reinterpret_cast<const v4u*>(sw_stage + off4(wave * 32 + r, 2 * gq + h));
+#pragma unroll
+      for (int i = 0; i < TI; ++i) {
+        const int row = i * 32 + r;
+        const v4u ap = *reinterpret_cast<const v4u*>(sa + C::A_LO + off4(row, 2 * gq + h));
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const v4i bw = widen(wp, s2);
+          const v4i ah = *reinterpret_cast<const v4i*>(sa + C::A_HI + off8(row, 4 * gq + 2 * h + s2));
+          acc_lo[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(widen(ap, s2), bw, acc_lo[i], 0, 0, 0);
+          acc_hi[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ah, bw, acc_hi[i], 0, 0, 0);
+        }
+      }
+    }
+    if (fill) pipeline_barrier<C::NA>();
+    else pipeline_barrier<0>();
+  }
+
+  // epilogue: the outputs are few (M <= 64 rows); plain stores
+  if (n < g.N) {
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int m = i * 32 + 8 * (q >> 2) + 4 * h + (q & 3);
+        if (m < g.M) {
+          float t = __fmul_rn(static_cast<float>(acc_lo[i][q]), slo[i][q]);
+          t = __fmaf_rn(static_cast<float>(acc_hi[i][q]), shi[i][q], t);
+          const float y = __fmul_rn(t, sw);
+          const int64_t o = static_cast<int64_t>(m) * g.ldy + n;
+          if (g.out_bf16) reinterpret_cast<uint16_t*>(g.y)[o] = bf16_rne(y);
+          else reinterpret_cast<float*>(g.y)[o] = y;
+          if (g.acc_lo_dbg) g.acc_lo_dbg[static_cast<int64_t>(m) * g.N + n] = acc_lo[i][q] >> 8;
+          if (g.acc_hi_dbg) g.acc_hi_dbg[static_cast<int64_t>(m) * g.N + n] = acc_hi[i][q] >> 4;
+        }
+      }
+  }
+}
+
+template <int TI>
+int launch_skinny(const GemmArgs& g, hipStream_t st) {
+  typedef SkinnyCfg<TI> C;
+  static bool attr_done[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return SQ_ERR_LAUNCH;
+  if (!attr_done[dev]) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<TI>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) != hipSuccess)
+      return SQ_ERR_LAUNCH;
+    attr_done[dev] = true;
+  }
+  hipLaunchKernelGGL((gemm_skinny_kernel<TI>), dim3((g.N + C::BN - 1) / C::BN), dim3(C::THREADS), C::LDS_BYTES, st, g);
+  return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
 }  // namespace
 
 int launch_gemm(const GemmArgs& g, hipStream_t st) {
-  typedef Tile<128, 256> Big;
-  if (g.a_lo && g.a_hi_dense) return launch_mode<Big, 0>(g, st);
-  if (g.a_lo && g.a_hi_compact) return launch_mode<Big, 1>(g, st);
-  if (!g.a_lo && g.a_hi_compact) return launch_mode<Big, 2>(g, st);
+  typedef Tile<128, 256> Big;   // matrix-core bound shapes
+  typedef Tile<64, 64> Skinny;  // M <= 64 (decode): bound by streaming the INT4 weights once from HBM, so the
+                                // tile is narrow in N to spread the weight rows over every compute unit
+                                // (several small workgroups per unit keep enough loads in flight)
+  const bool skinny = g.M <= 64;
+  if (g.a_lo && g.a_hi_dense) {
+    if (g.M <= 32 && g.K % KS == 0) return launch_skinny<1>(g, st);
+    return skinny ? launch_mode<Skinny, 0>(g, st) : launch_mode<Big, 0>(g, st);
+  }
+  if (g.a_lo && g.a_hi_compact) return skinny ? launch_mode<Skinny, 1>(g, st) : launch_mode<Big, 1>(g, st);
+  if (!g.a_lo && g.a_hi_compact) return skinny ? launch_mode<Skinny, 2>(g, st) : launch_mode<Big, 2>(g, st);
   return SQ_ERR_UNSUPPORTED;
 }
 
