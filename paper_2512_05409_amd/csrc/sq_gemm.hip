@@ -280,18 +280,21 @@ __device__ __forceinline__ void k_iteration(const Pipe<T, LO, HI>& pipe, char* l
 // two iterations are peeled so that the steady-state body has no branches.
 // Safety: the stage overwritten by the copy of step kt+2 was last read (step kt-1) before the
 // barrier of iteration kt-1, and every wave drains its LDS reads (lgkmcnt 0) before that barrier.
+// k_loop_start enqueues the first two steps; k_loop expects them enqueued (whatever independent work the
+// caller has goes between the two calls, under the latency of those first copies).
+template <typename T, bool LO, bool HI>
+__device__ __forceinline__ void k_loop_start(const Pipe<T, LO, HI>& pipe, char* lds) {
+  pipe.template issue<true>(lds, 0);
+  if (pipe.kext > KS) pipe.template issue<true>(lds + T::STAGE, 1);
+}
+
 template <typename T, bool LO, bool HI>
 __device__ __forceinline__ void k_loop(const Pipe<T, LO, HI>& pipe, char* lds, int wm, int wn, int lane,
                                        v16i (&acc_lo)[T::TI][T::TJ], v16i (&acc_hi)[T::TI][T::TJ]) {
   constexpr int NL = Pipe<T, LO, HI>::NLOAD;
   const int steps = (pipe.kext + KS - 1) / KS;
-  pipe.template issue<true>(lds, 0);
-  if (steps > 1) {
-    pipe.template issue<true>(lds + T::STAGE, 1);
-    pipeline_barrier<NL>();
-  } else {
-    pipeline_barrier<0>();
-  }
+  if (steps > 1) pipeline_barrier<NL>();
+  else pipeline_barrier<0>();
   Frags<T> f0, f1;
   Wide<T> w0, w1;
   read_frags<T, LO, HI>(f0, lds, 0, wm, wn, lane);
@@ -352,10 +355,33 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm,
 // lane holds single elements of many rows.  The per-token scales of the workgroup's rows and the
 // finished outputs go through LDS (free after the K loops): every wave transposes 32 rows x WN columns
 // at a time and then stores 16 bytes per lane, whole row segments at once.
+// The scales a thread contributes to the epilogue, fetched at the start of the kernel so that their
+// latency hides under the K loop.
+template <typename T>
+struct EpiScales {
+  float slo, shi;    // thread t < BM: s_lo / 256 and s_hi / 16 of row m0 + t
+  float sw[T::TJ];   // s_w of this lane's column in each of the wave's 32-column tiles
+};
+
+template <typename T>
+__device__ __forceinline__ void load_epi_scales(EpiScales<T>& e, const GemmArgs& g, int m0, int n0, int wn, int lane) {
+  // The accumulators carry the widening factors (256 and 16); folding the inverse powers of two into the
+  // scales is exact and leaves every rounding of the epilogue where it was.
+  const int tid = threadIdx.x;
+  const int m = min(m0 + (tid < T::BM ? tid : 0), g.M - 1);
+  e.slo = g.s_lo ? g.s_lo[m] * (1.0f / 256.0f) : 0.0f;
+  e.shi = g.s_hi[m] * (1.0f / 16.0f);
+#pragma unroll
+  for (int j = 0; j < T::TJ; ++j) {
+    const int n = n0 + wn * T::WN + j * 32 + (lane & 31);
+    e.sw[j] = g.s_w[min(n, g.N - 1)];
+  }
+}
+
 template <typename T, typename OutT>
-__device__ __forceinline__ void epilogue_typed(const GemmArgs& g, char* lds, v16i (&acc_lo)[T::TI][T::TJ],
-                                               v16i (&acc_hi)[T::TI][T::TJ], int m0, int n0, int wm, int wn, int wave,
-                                               int lane) {
+__device__ __forceinline__ void epilogue_typed(const GemmArgs& g, const EpiScales<T>& es, char* lds,
+                                               v16i (&acc_lo)[T::TI][T::TJ], v16i (&acc_hi)[T::TI][T::TJ], int m0, int n0,
+                                               int wm, int wn, int wave, int lane) {
   constexpr int ESZ = sizeof(OutT);
   constexpr int ROW = T::WN * ESZ + 16;   // padded row of the transposition buffer (bytes)
   constexpr int PER16 = 16 / ESZ;         // outputs per 16-byte store
@@ -366,19 +392,10 @@ __device__ __forceinline__ void epilogue_typed(const GemmArgs& g, char* lds, v16
   float* sc = reinterpret_cast<float*>(lds);  // [0, BM): s_lo, [BM, 2 BM): s_hi   (BM <= 128)
   char* tb = lds + 1024 + wave * (32 * ROW);
   if (tid < T::BM) {
-    // The accumulators still carry the widening factors (256 and 16); folding the inverse powers of two
-    // into the scales is exact and leaves every rounding of the epilogue where it was.
-    const int m = min(m0 + tid, g.M - 1);
-    sc[tid] = g.s_lo ? g.s_lo[m] * (1.0f / 256.0f) : 0.0f;
-    sc[T::BM + tid] = g.s_hi[m] * (1.0f / 16.0f);
+    sc[tid] = es.slo;
+    sc[T::BM + tid] = es.shi;
   }
   __syncthreads();
-  float sw[T::TJ];
-#pragma unroll
-  for (int j = 0; j < T::TJ; ++j) {
-    const int n = n0 + wn * T::WN + j * 32 + (lane & 31);
-    sw[j] = n < g.N ? g.s_w[n] : 0.0f;
-  }
   const bool vec_ok = (g.ldy % PER16) == 0;  // rows of Y stay 16-byte aligned
   OutT* yout = reinterpret_cast<OutT*>(g.y);
 #pragma unroll
@@ -396,7 +413,7 @@ __device__ __forceinline__ void epilogue_typed(const GemmArgs& g, char* lds, v16
         for (int j = 0; j < T::TJ; ++j) {
           float t = __fmul_rn(static_cast<float>(acc_lo[i][j][4 * rq + e]), slo[e]);
           t = __fmaf_rn(static_cast<float>(acc_hi[i][j][4 * rq + e]), shi[e], t);
-          const float y = __fmul_rn(t, sw[j]);
+          const float y = __fmul_rn(t, es.sw[j]);
           OutT* dst = reinterpret_cast<OutT*>(tb + (rl0 + e) * ROW) + j * 32 + (lane & 31);
           if constexpr (ESZ == 2) *dst = bf16_rne(y);
           else *dst = y;
@@ -439,10 +456,11 @@ __device__ __forceinline__ void epilogue_typed(const GemmArgs& g, char* lds, v16
 }
 
 template <typename T>
-__device__ __forceinline__ void epilogue(const GemmArgs& g, char* lds, v16i (&acc_lo)[T::TI][T::TJ],
-                                         v16i (&acc_hi)[T::TI][T::TJ], int m0, int n0, int wm, int wn, int wave, int lane) {
-  if (g.out_bf16) epilogue_typed<T, uint16_t>(g, lds, acc_lo, acc_hi, m0, n0, wm, wn, wave, lane);
-  else epilogue_typed<T, float>(g, lds, acc_lo, acc_hi, m0, n0, wm, wn, wave, lane);
+__device__ __forceinline__ void epilogue(const GemmArgs& g, const EpiScales<T>& es, char* lds,
+                                         v16i (&acc_lo)[T::TI][T::TJ], v16i (&acc_hi)[T::TI][T::TJ], int m0, int n0, int wm,
+                                         int wn, int wave, int lane) {
+  if (g.out_bf16) epilogue_typed<T, uint16_t>(g, es, lds, acc_lo, acc_hi, m0, n0, wm, wn, wave, lane);
+  else epilogue_typed<T, float>(g, es, lds, acc_lo, acc_hi, m0, n0, wm, wn, wave, lane);
 }
 
 // MODE 0: dynamic (low + zero-padded high in one K loop); 1: static (low loop over K, then the
@@ -458,6 +476,24 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmArgs g) {
   if (tm < 0) return;
   const int m0 = tm * T::BM, n0 = tn * T::BN;
 
+  // Order: scales first (they are the oldest vector-memory operations, so no later wait is held up by
+  // them), then the first copies of the K loop, then the accumulators are cleared under their latency.
+  EpiScales<T> es;
+  load_epi_scales<T>(es, g, m0, n0, wn, lane);
+  constexpr bool HI1 = MODE == 0;  // the first loop also carries the INT8 operand (dynamic mode)
+  Pipe<T, true, HI1> p1;           // MODE 0: low + zero-padded high; MODE 1: low only; MODE 2: unused
+  Pipe<T, false, true> p2;         // MODE 1, 2: the compact high loop
+  if constexpr (MODE == 0) {
+    p1.init(g.a_lo, g.K / 2, g.a_hi_dense, g.K, g.wq, g.K / 2, g.K, m0, n0, g.M, g.N);
+    k_loop_start<T, true, HI1>(p1, lds);
+  } else if constexpr (MODE == 1) {
+    p1.init(g.a_lo, g.K / 2, nullptr, 0, g.wq, g.K / 2, g.K, m0, n0, g.M, g.N);
+    k_loop_start<T, true, HI1>(p1, lds);
+  } else {
+    p2.init(nullptr, 0, g.a_hi_compact, g.lda_hi_compact, g.w_hi, g.K_hi / 2, g.K_hi, m0, n0, g.M, g.N);
+    k_loop_start<T, false, true>(p2, lds);
+  }
+
   v16i acc_lo[T::TI][T::TJ], acc_hi[T::TI][T::TJ];
 #pragma unroll
   for (int i = 0; i < T::TI; ++i)
@@ -469,22 +505,18 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmArgs g) {
         acc_hi[i][j][r] = 0;
       }
 
-  if (MODE == 0) {
-    Pipe<T, true, true> pipe;
-    pipe.init(g.a_lo, g.K / 2, g.a_hi_dense, g.K, g.wq, g.K / 2, g.K, m0, n0, g.M, g.N);
-    k_loop<T, true, true>(pipe, lds, wm, wn, lane, acc_lo, acc_hi);
+  if constexpr (MODE == 0) {
+    k_loop<T, true, HI1>(p1, lds, wm, wn, lane, acc_lo, acc_hi);
   } else {
-    if (MODE == 1) {
-      Pipe<T, true, false> p1;
-      p1.init(g.a_lo, g.K / 2, nullptr, 0, g.wq, g.K / 2, g.K, m0, n0, g.M, g.N);
-      k_loop<T, true, false>(p1, lds, wm, wn, lane, acc_lo, acc_hi);
+    if constexpr (MODE == 1) {
+      k_loop<T, true, HI1>(p1, lds, wm, wn, lane, acc_lo, acc_hi);
+      p2.init(nullptr, 0, g.a_hi_compact, g.lda_hi_compact, g.w_hi, g.K_hi / 2, g.K_hi, m0, n0, g.M, g.N);
+      k_loop_start<T, false, true>(p2, lds);
     }
-    Pipe<T, false, true> p2;
-    p2.init(nullptr, 0, g.a_hi_compact, g.lda_hi_compact, g.w_hi, g.K_hi / 2, g.K_hi, m0, n0, g.M, g.N);
     k_loop<T, false, true>(p2, lds, wm, wn, lane, acc_lo, acc_hi);
   }
 
-  epilogue<T>(g, lds, acc_lo, acc_hi, m0, n0, wm, wn, wave, lane);
+  epilogue<T>(g, es, lds, acc_lo, acc_hi, m0, n0, wm, wn, wave, lane);
 }
 
 template <typename T, int MODE>
