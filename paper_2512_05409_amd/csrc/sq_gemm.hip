@@ -745,13 +745,23 @@ int launch_gemm(const GemmArgs& g, hipStream_t st) {
   typedef Tile<64, 64> Skinny;  // M <= 64 (decode): bound by streaming the INT4 weights once from HBM, so the
                                 // tile is narrow in N to spread the weight rows over every compute unit
                                 // (several small workgroups per unit keep enough loads in flight)
+  typedef Tile<128, 128> Mid;   // shapes with too few 128x256 tiles to occupy every compute unit
   const bool skinny = g.M <= 64;
+  const int64_t big_tiles = static_cast<int64_t>((g.M + 127) / 128) * ((g.N + 255) / 256);
+  const bool mid = !skinny && big_tiles <= 128;  // then twice as many half-size tiles still run in one round
   if (g.a_lo && g.a_hi_dense) {
     if (g.M <= 32 && g.K % KS == 0) return launch_skinny<1>(g, st);
-    return skinny ? launch_mode<Skinny, 0>(g, st) : launch_mode<Big, 0>(g, st);
+    if (skinny) return launch_mode<Skinny, 0>(g, st);
+    return mid ? launch_mode<Mid, 0>(g, st) : launch_mode<Big, 0>(g, st);
   }
-  if (g.a_lo && g.a_hi_compact) return skinny ? launch_mode<Skinny, 1>(g, st) : launch_mode<Big, 1>(g, st);
-  if (!g.a_lo && g.a_hi_compact) return skinny ? launch_mode<Skinny, 2>(g, st) : launch_mode<Big, 2>(g, st);
+  if (g.a_lo && g.a_hi_compact) {
+    if (skinny) return launch_mode<Skinny, 1>(g, st);
+    return mid ? launch_mode<Mid, 1>(g, st) : launch_mode<Big, 1>(g, st);
+  }
+  if (!g.a_lo && g.a_hi_compact) {
+    if (skinny) return launch_mode<Skinny, 2>(g, st);
+    return mid ? launch_mode<Mid, 2>(g, st) : launch_mode<Big, 2>(g, st);
+  }
   return SQ_ERR_UNSUPPORTED;
 }
 
