@@ -545,10 +545,13 @@ int launch_mode(const GemmArgs& g, hipStream_t st) {
 // Vector-memory operations of a wave retire in order, so one wave cannot keep a deep queue of weight
 // loads and, at the same time, wait for the shallow queue of (L2-resident) activation loads.  The
 // workgroup is therefore specialised: waves 0 and 1 multiply (32 output channels each, all tokens)
-// and copy the activation tiles two K steps ahead; wave 2 only copies weights, seven K steps ahead,
+// and copy the activation tiles three K steps ahead; wave 2 only copies weights, seven K steps ahead,
 // into its own ring of eight LDS stages.  Each wave waits on its own counter; one workgroup barrier
-// per K step publishes both copies.  A workgroup covers 64 output channels, so N/64 workgroups
-// (two or three per compute unit) stream disjoint weight rows.
+// per K step publishes both copies.  Both copies are published one step earlier than they are
+// multiplied, so that a consumer fetches the operands of step kt+1 from LDS while the matrix
+// instructions of step kt run: the per-step chain "barrier -> LDS read -> multiply -> barrier", which
+// otherwise bounds the streaming rate at N * 64 bytes per chain time, shrinks to the multiply.
+// A workgroup covers 64 output channels, so N/64 workgroups (two per compute unit) stream disjoint rows.
 // TI = number of 32-token blocks (1: M <= 32, 2: M <= 64).  Requires K % 128 == 0.
 template <int TI>
 struct SkinnyCfg {
@@ -557,7 +560,7 @@ struct SkinnyCfg {
   static constexpr int A_LO = 0;
   static constexpr int A_HI = BM * 64;
   static constexpr int A_STAGE = BM * 192;
-  static constexpr int A_STAGES = 3;
+  static constexpr int A_STAGES = 4;
   static constexpr int W_OFF = A_STAGES * A_STAGE;
   static constexpr int W_STAGE = BN * 64;
   static constexpr int W_STAGES = 8;
@@ -614,15 +617,16 @@ __global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
       const int c = ((lane & 3) ^ (row >> 2)) & 3;
       src[q] = reinterpret_cast<const char*>(g.wq) + static_cast<int64_t>(min(n0 + row, g.N - 1)) * (g.K / 2) + c * 16;
     }
+    // at barrier kt (the prologue barrier is kt = -1) the copies of steps <= kt+2 have landed
     const int pre = min(C::W_AHEAD, steps);
     for (int s2 = 0; s2 < pre; ++s2) skinny_issue_w<TI>(src, lds, s2);
-    if (pre == C::W_AHEAD) pipeline_barrier<4 * (C::W_AHEAD - 1)>();  // step 0 has landed
+    if (pre == C::W_AHEAD) pipeline_barrier<4 * (C::W_AHEAD - 2)>();
     else pipeline_barrier<0>();
     for (int kt = 0; kt < steps; ++kt) {
       if (kt + C::W_AHEAD < steps) {
         const int ahead = kt + W_AHEAD;
         skinny_issue_w<TI>(src, lds, ahead);
-        pipeline_barrier<4 * (C::W_AHEAD - 1)>();  // step kt+1 has landed, six younger steps stay in flight
+        pipeline_barrier<4 * (C::W_AHEAD - 2)>();  // five younger steps stay in flight
       } else {
         pipeline_barrier<0>();
       }
@@ -669,37 +673,64 @@ __global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
       acc_hi[i][q] = 0;
     }
 
+  // at barrier kt (prologue: kt = -1) this wave's activation copies of steps <= kt+2 have landed
   skinny_issue_a<TI>(p_lo, p_hi, lds, 0, wave);
-  if (steps > 1) {
-    skinny_issue_a<TI>(p_lo, p_hi, lds, 1, wave);
+  if (steps > 1) skinny_issue_a<TI>(p_lo, p_hi, lds, 1, wave);
+  if (steps > 2) {
+    skinny_issue_a<TI>(p_lo, p_hi, lds, 2, wave);
     pipeline_barrier<C::NA>();
   } else {
     pipeline_barrier<0>();
   }
-  for (int kt = 0; kt < steps; ++kt) {
-    const bool fill = kt + 2 < steps;
-    if (fill) skinny_issue_a<TI>(p_lo, p_hi, lds, kt + 2, wave);
-    const char* sa = lds + (kt % C::A_STAGES) * C::A_STAGE;
-    const char* sw_stage = lds + C::W_OFF + (kt % C::W_STAGES) * C::W_STAGE;
-#pragma unroll
-    for (int gq = 0; gq < 2; ++gq) {
-      const v4u wp = *reinterpret_cast<const v4u*>(sw_stage + off4(wave * 32 + r, 2 * gq + h));
-#pragma unroll
-      for (int i = 0; i < TI; ++i) {
-        const int row = i * 32 + r;
-        const v4u ap = *reinterpret_cast<const v4u*>(sa + C::A_LO + off4(row, 2 * gq + h));
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          const v4i bw = widen(wp, s2);
-          const v4i ah = *reinterpret_cast<const v4i*>(sa + C::A_HI + off8(row, 4 * gq + 2 * h + s2));
-          acc_lo[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(widen(ap, s2), bw, acc_lo[i], 0, 0, 0);
-          acc_hi[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ah, bw, acc_hi[i], 0, 0, 0);
-        }
-      }
+  // operands of one K step, fetched from LDS one step ahead of the matrix instructions that use them
+  v4u fw[2][2], fa[2][TI][2];
+  v4i fh[2][TI][4];
+#define SQ_SKINNY_FETCH(buf, step)                                                                        \
+  do {                                                                                                    \
+    const char* sa_ = lds + ((step) % C::A_STAGES) * C::A_STAGE;                                          \
+    const char* sw_ = lds + C::W_OFF + ((step) % C::W_STAGES) * C::W_STAGE;                               \
+    _Pragma("unroll") for (int gq = 0; gq < 2; ++gq) {                                                    \
+      fw[buf][gq] = *reinterpret_cast<const v4u*>(sw_ + off4(wave * 32 + r, 2 * gq + h));                 \
+      _Pragma("unroll") for (int i = 0; i < TI; ++i) {                                                    \
+        fa[buf][i][gq] = *reinterpret_cast<const v4u*>(sa_ + C::A_LO + off4(i * 32 + r, 2 * gq + h));     \
+        fh[buf][i][2 * gq] = *reinterpret_cast<const v4i*>(sa_ + C::A_HI + off8(i * 32 + r, 4 * gq + 2 * h));          \
+        fh[buf][i][2 * gq + 1] = *reinterpret_cast<const v4i*>(sa_ + C::A_HI + off8(i * 32 + r, 4 * gq + 2 * h + 1));  \
+      }                                                                                                   \
+    }                                                                                                     \
+  } while (0)
+#define SQ_SKINNY_MMA(buf)                                                                                \
+  do {                                                                                                    \
+    _Pragma("unroll") for (int gq = 0; gq < 2; ++gq) _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {   \
+      const v4i bw_ = widen(fw[buf][gq], s2);                                                             \
+      _Pragma("unroll") for (int i = 0; i < TI; ++i) {                                                    \
+        acc_lo[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(widen(fa[buf][i][gq], s2), bw_, acc_lo[i], 0, 0, 0);  \
+        acc_hi[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fh[buf][i][2 * gq + s2], bw_, acc_hi[i], 0, 0, 0);    \
+      }                                                                                                   \
+    }                                                                                                     \
+  } while (0)
+  SQ_SKINNY_FETCH(0, 0);
+  for (int kt = 0; kt < steps; kt += 2) {  // two steps per trip: the operand buffers alternate statically
+    if (kt + 1 < steps) SQ_SKINNY_FETCH(1, kt + 1);
+    if (kt + 3 < steps) {
+      const int ahead = kt + 3;
+      skinny_issue_a<TI>(p_lo, p_hi, lds, ahead, wave);
     }
-    if (fill) pipeline_barrier<C::NA>();
+    SQ_SKINNY_MMA(0);
+    if (kt + 3 < steps) pipeline_barrier<C::NA>();
     else pipeline_barrier<0>();
+    if (kt + 1 < steps) {
+      if (kt + 2 < steps) SQ_SKINNY_FETCH(0, kt + 2);
+      if (kt + 4 < steps) {
+        const int ahead = kt + 4;
+        skinny_issue_a<TI>(p_lo, p_hi, lds, ahead, wave);
+      }
+      SQ_SKINNY_MMA(1);
+      if (kt + 4 < steps) pipeline_barrier<C::NA>();
+      else pipeline_barrier<0>();
+    }
   }
+#undef SQ_SKINNY_FETCH
+#undef SQ_SKINNY_MMA
 
   // epilogue: the outputs are few (M <= 64 rows); plain stores
   if (n < g.N) {
