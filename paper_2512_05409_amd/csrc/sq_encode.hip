@@ -43,6 +43,35 @@ __device__ __forceinline__ void bitonic_sort_desc(uint32_t* v) {
   }
 }
 
+__device__ __forceinline__ void cex_desc(uint32_t* v, int i, int j) {  // larger value to the lower index
+  const uint32_t a = v[i], b = v[j];
+  v[i] = umax(a, b);
+  v[j] = umin(a, b);
+}
+
+// Sorts v[0..N) descending with the smallest known comparator networks for N = 2, 4, 8 (1, 5, 19
+// exchanges instead of the bitonic 1, 6, 24); larger N fall back to the bitonic network.
+template <int N>
+__device__ __forceinline__ void sort_desc(uint32_t* v) {
+  if constexpr (N == 2) {
+    cex_desc(v, 0, 1);
+  } else if constexpr (N == 4) {
+    cex_desc(v, 0, 1); cex_desc(v, 2, 3);
+    cex_desc(v, 0, 2); cex_desc(v, 1, 3);
+    cex_desc(v, 1, 2);
+  } else if constexpr (N == 8) {
+    cex_desc(v, 0, 1); cex_desc(v, 2, 3); cex_desc(v, 4, 5); cex_desc(v, 6, 7);
+    cex_desc(v, 0, 2); cex_desc(v, 1, 3); cex_desc(v, 4, 6); cex_desc(v, 5, 7);
+    cex_desc(v, 1, 2); cex_desc(v, 5, 6); cex_desc(v, 0, 4); cex_desc(v, 3, 7);
+    cex_desc(v, 1, 5); cex_desc(v, 2, 6);
+    cex_desc(v, 1, 4); cex_desc(v, 3, 6);
+    cex_desc(v, 2, 4); cex_desc(v, 3, 5);
+    cex_desc(v, 3, 4);
+  } else {
+    bitonic_sort_desc<N>(v);
+  }
+}
+
 // v[0..N) is bitonic; sorts it descending.
 template <int N>
 __device__ __forceinline__ void bitonic_merge_desc(uint32_t* v) {
@@ -60,11 +89,6 @@ __device__ __forceinline__ void bitonic_merge_desc(uint32_t* v) {
   }
 }
 
-// fp32 value of a bf16 given as (15-bit magnitude, sign in bit 0 of `sign_lsb`).
-__device__ __forceinline__ float bf16_from_key(uint32_t key) {
-  return __uint_as_float(((key >> 9) << 16) | (key << 31));
-}
-
 // 8 mask bits -> 8 nibbles of all-ones / all-zeros.
 __device__ __forceinline__ uint32_t spread_bits_to_nibbles(uint32_t b8) {
   uint32_t t = b8 & 0xFFu;
@@ -74,7 +98,9 @@ __device__ __forceinline__ uint32_t spread_bits_to_nibbles(uint32_t b8) {
   return (t << 4) - t;  // each 1 -> 0xF
 }
 
-// Low-part codes of 8 consecutive channels (4 packed bf16 pairs) as one dword of nibbles.
+// Low-part codes of 8 consecutive channels (4 packed bf16 pairs) as one dword of nibbles.  The channels
+// of the high part come through here too, with quotients far outside [-7, 7]: only the low four bits
+// of each rounded value are kept, and the caller clears those nibbles.
 __device__ __forceinline__ uint32_t quant_lo8(const uint32_t* pairs, float inv_lo) {
   uint32_t acc = 0;
 #pragma unroll
@@ -122,6 +148,37 @@ __device__ __forceinline__ BankCoord bank_coord(int G, int R, int M) {
   return c;
 }
 
+// Selection key of one element: magnitude (15 bits of the bf16) in bits 31..17, 255 - channel in bits
+// 8..1, the sign in bit 0.  Keys of one bank are distinct, larger magnitude sorts first and among equal
+// magnitudes the lower channel does (Section 3.1, the top-k rule with ties to the lower index).
+// `rot` is the bf16 pair rotated so that the wanted element's magnitude sits in bits 31..17 and its
+// sign in bit 0.
+__device__ __forceinline__ uint32_t make_key(uint32_t rot, uint32_t ch) {
+  return (rot & 0xFFFE0001u) | ((255u - ch) << 1);
+}
+__device__ __forceinline__ uint32_t key_channel(uint32_t key) { return 255u - ((key >> 1) & 255u); }
+__device__ __forceinline__ uint32_t key_magnitude(uint32_t key) { return key >> 17; }
+__device__ __forceinline__ float key_value(uint32_t key) {  // the element as fp32
+  return __uint_as_float(__builtin_amdgcn_alignbit(key, key, 1) & 0xFFFF0000u);
+}
+
+template <int B>
+__device__ __forceinline__ void load_bank(const uint16_t* __restrict__ x, int64_t ldx, int64_t row, int g, uint32_t* xr) {
+  const uint4* src = reinterpret_cast<const uint4*>(x + row * ldx + static_cast<int64_t>(g) * B);
+#pragma unroll
+  for (int i = 0; i < B / 8; ++i) {
+    const uint4 v = src[i];
+    xr[4 * i + 0] = v.x;
+    xr[4 * i + 1] = v.y;
+    xr[4 * i + 2] = v.z;
+    xr[4 * i + 3] = v.w;
+  }
+}
+
+// Dynamic rule (Section 3.1, Eq. (1) with the per-bank top-k mask).  More blocks than the chip holds at
+// once are launched for the large shapes, so that the fetches and stores of one block overlap the
+// arithmetic of another; a variant in which a block walked over several row groups and fetched the next
+// one ahead was slower at every size.
 template <int B, int KT, int MAXT>
 __global__ __launch_bounds__(MAXT) void encode_dynamic_kernel(const uint16_t* __restrict__ x, int64_t ldx, int M, int K,
                                                               int G, int R, uint8_t* __restrict__ d_lo,
@@ -136,26 +193,18 @@ __global__ __launch_bounds__(MAXT) void encode_dynamic_kernel(const uint16_t* __
   const BankCoord c = bank_coord(G, R, M);
 
   uint32_t xr[B / 2];  // the bank: bf16 pairs, channel 2i in the low half of xr[i]
-  uint32_t top[KT];    // the k largest keys, descending
+  uint32_t top[KT];    // the k largest keys (unordered)
   if (c.active) {
-    const uint4* src = reinterpret_cast<const uint4*>(x + c.row * ldx + static_cast<int64_t>(c.g) * B);
-#pragma unroll
-    for (int i = 0; i < B / 8; ++i) {
-      const uint4 v = src[i];
-      xr[4 * i + 0] = v.x;
-      xr[4 * i + 1] = v.y;
-      xr[4 * i + 2] = v.z;
-      xr[4 * i + 3] = v.w;
-    }
+    load_bank<B>(x, ldx, c.row, c.g, xr);
     uint32_t key[B];
 #pragma unroll
     for (int i = 0; i < B / 2; ++i) {
       const uint32_t w = xr[i];
-      key[2 * i] = ((w & 0x7FFFu) << 9) | ((255u - 2 * i) << 1) | ((w >> 15) & 1u);
-      key[2 * i + 1] = (((w >> 16) & 0x7FFFu) << 9) | ((255u - (2 * i + 1)) << 1) | (w >> 31);
+      key[2 * i] = make_key(__builtin_amdgcn_alignbit(w, w, 15), 2 * i);
+      key[2 * i + 1] = make_key(__builtin_amdgcn_alignbit(w, w, 31), 2 * i + 1);
     }
 #pragma unroll
-    for (int g0 = 0; g0 < B; g0 += KT) bitonic_sort_desc<KT>(key + g0);
+    for (int g0 = 0; g0 < B; g0 += KT) sort_desc<KT>(key + g0);
     uint32_t dropped[KT];
 #pragma unroll
     for (int i = 0; i < KT; ++i) dropped[i] = 0;
@@ -171,16 +220,21 @@ __global__ __launch_bounds__(MAXT) void encode_dynamic_kernel(const uint16_t* __
           a[i] = umax(ai, bj);
           dropped[i] = umax(dropped[i], umin(ai, bj));
         }
-        bitonic_merge_desc<KT>(a);
+        // the survivors form a bitonic sequence; the next merge needs them sorted, the last one only
+        // needs the set (the high codes are re-ordered by channel anyway)
+        if (2 * width < B) bitonic_merge_desc<KT>(a);
       }
     }
-    uint32_t dmax = dropped[0];
+    uint32_t dmax = dropped[0], tmax = key[0];
 #pragma unroll
-    for (int i = 1; i < KT; ++i) dmax = umax(dmax, dropped[i]);
+    for (int i = 1; i < KT; ++i) {
+      dmax = umax(dmax, dropped[i]);
+      tmax = umax(tmax, key[i]);
+    }
 #pragma unroll
     for (int i = 0; i < KT; ++i) top[i] = key[i];
-    atomicMax(&amax_sh[2 * c.r_local], top[0] >> 9);
-    atomicMax(&amax_sh[2 * c.r_local + 1], dmax >> 9);
+    atomicMax(&amax_sh[2 * c.r_local], key_magnitude(tmax));
+    atomicMax(&amax_sh[2 * c.r_local + 1], key_magnitude(dmax));
   }
   __syncthreads();
   if (!c.active) return;
@@ -201,9 +255,8 @@ __global__ __launch_bounds__(MAXT) void encode_dynamic_kernel(const uint16_t* __
   for (int w = 0; w < B / 32; ++w) mw[w] = 0;
 #pragma unroll
   for (int t = 0; t < KT; ++t) {
-    const uint32_t key = top[t];
-    const uint32_t ch = 255u - ((key >> 1) & 255u);
-    const float v = __fmul_rn(bf16_from_key(key), inv_hi);
+    const uint32_t ch = key_channel(top[t]);
+    const float v = __fmul_rn(key_value(top[t]), inv_hi);
     const float r = __fadd_rn(v, kRoundMagic);
     ent[t] = (ch << 8) | (__float_as_uint(r) & 0xFFu);
 #pragma unroll
@@ -212,7 +265,8 @@ __global__ __launch_bounds__(MAXT) void encode_dynamic_kernel(const uint16_t* __
   if (hi_dense) {
     // Matrix-core-ready image of the bank's high part: zeros, then the k codes scattered to their
     // channels (inside every group of 8 channels: the even ones, then the odd ones).  The scatter goes
-    // through LDS, where a lane can address bytes dynamically; chunk c of lane t sits at (c * blockDim + t) * 16.
+    // through LDS, where a lane can address bytes dynamically; chunk c of lane t sits at
+    // (c * blockDim + t) * 16, an area no other lane touches.
     const int nt = blockDim.x, t = threadIdx.x;
 #pragma unroll
     for (int ch16 = 0; ch16 < B / 16; ++ch16)
@@ -227,7 +281,7 @@ __global__ __launch_bounds__(MAXT) void encode_dynamic_kernel(const uint16_t* __
 #pragma unroll
     for (int ch16 = 0; ch16 < B / 16; ++ch16) hd[ch16] = *reinterpret_cast<const uint4*>(dense_stage + (ch16 * nt + t) * 16);
   }
-  bitonic_sort_desc<KT>(ent);  // descending channel; read back reversed
+  sort_desc<KT>(ent);  // descending channel; read back reversed
   uint32_t hv[(KT + 3) / 4];
 #pragma unroll
   for (int i = 0; i < (KT + 3) / 4; ++i) hv[i] = 0;
