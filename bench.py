@@ -25,6 +25,16 @@ if ROOT not in sys.path:
 INT8_PEAK_TOPS = 5000.0  # MI355X dense INT8 matrix peak (vendor figure, no sparsity), TOP/s
 HBM_PEAK_GBS = 8000.0    # MI355X HBM3E peak, GB/s
 
+# HBM-side bytes per sq_gemm launch, from rocprofv3's FETCH_SIZE and WRITE_SIZE counters (two runs of this
+# script per workload, summaries under profiles/), each scaled by what the same counter reads for a plain
+# device copy of known size (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Counters cannot be read from inside
+# this process, so the figures are the recorded ones; they apply to the unmodified workload shapes only.
+MEASURED_GEMM_TRAFFIC = {
+    "c3": {"fetch_bytes": 646.6e6, "write_bytes": 222.6e6, "source": "profiles/sq_linear_c3_mlp7b.md"},
+    "c4": {"fetch_bytes": 260.3e6, "write_bytes": 37.2e6, "source": "profiles/sq_linear_c4_down7b_static.md"},
+    "c5": {"fetch_bytes": 3313.9e6, "write_bytes": 579.9e6, "source": "profiles/sq_linear_c5_up70b.md"},
+}
+
 WORKLOADS = {
     "c2": ("c2_qkv7b", {}),
     "c3": ("c3_mlp7b", {}),
@@ -194,6 +204,15 @@ def main():
     enc_bytes = M * K * 2 + M * K // 2 + M * (K // b) * k + (0 if static else M * K // 8) + 8 * M
     enc_bytes_written_extra = 0 if static else M * K  # the matrix-core-ready image of the high part
 
+    traffic, traffic_detail = None, None
+    if args.workload in MEASURED_GEMM_TRAFFIC and args.M is None and args.bank is None and args.topk is None:
+        traffic_detail = dict(MEASURED_GEMM_TRAFFIC[args.workload])
+        traffic = traffic_detail["fetch_bytes"] + traffic_detail["write_bytes"]
+        # what one launch has to move at least: both activation operands, the weights, the scales, the output
+        a_bytes = M * K // 2 + (M * (K // b) * k if static else M * K)
+        w_bytes = N * K // 2 + (N * (K // b) * k // 2 if static else 0)
+        traffic_detail["compulsory_bytes"] = a_bytes + w_bytes + 8 * M + 4 * N + 2 * M * N
+
     out = {
         "metric": "SQ-format linear effective TOPS (encode+GEMM) and % of INT8 MFMA peak, 1 GPU",
         "value": eff_tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -205,7 +224,8 @@ def main():
                    "x_buffers_rotated": n_x},
         "pct_int8_peak_effective": 100.0 * eff_tops / INT8_PEAK_TOPS,
         "roofline": {"kernel": "sq_gemm", "bound": "mfma", "achieved": alg_ops / gemm_s / 1e12, "peak": INT8_PEAK_TOPS,
-                     "unit": "TOP/s", "frac": alg_ops / gemm_s / 1e12 / INT8_PEAK_TOPS, "traffic": None,
+                     "unit": "TOP/s", "frac": alg_ops / gemm_s / 1e12 / INT8_PEAK_TOPS, "traffic": traffic,
+                     "traffic_detail": traffic_detail,
                      "ms": gemm_s * 1e3, "ms_min": float(gemm_ms.min()),
                      "algorithmic_ops": alg_ops, "issued_mfma_ops": issued_ops,
                      "issued_frac": issued_ops / gemm_s / 1e12 / INT8_PEAK_TOPS,
