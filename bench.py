@@ -54,6 +54,7 @@ def parse():
     ap.add_argument("--topk", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-baseline", action="store_true")
+    ap.add_argument("--no-probes", action="store_true", help="skip the measured matrix-instruction and streaming rates")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the CPU-oracle sample (0: sized for about 20 s)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of 256 MiB (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -104,6 +105,41 @@ def cpu_baseline(wl, mask, rows_req):
     }
 
 
+def probes(torch, sq, xs, enc_write_bytes):
+    """What the chip sustains, measured here, beside the vendor peaks: the products' matrix instruction on
+    register operands, and a plain streaming kernel with the encoder's mix of bytes read and written."""
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    blocks, iters = 2 * n_cu, 2000
+    sink = torch.empty(blocks * 256, dtype=torch.int32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    sq.sq_probe_mfma_i8(blocks, iters, sink)
+    torch.cuda.synchronize()
+    e0.record()
+    sq.sq_probe_mfma_i8(blocks, iters, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    mfma_tops = 2.0 * 32768 * 8 * iters * 4 * blocks / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+    read_bytes = xs[0].numel() * xs[0].element_size()
+    write_bytes = (int(enc_write_bytes) + 15) // 16 * 16
+    dst = torch.empty(max(16, write_bytes), dtype=torch.uint8, device="cuda")
+    for i in range(3):
+        sq.sq_probe_stream(xs[i % len(xs)], read_bytes, dst, write_bytes)
+    torch.cuda.synchronize()
+    reps = 30
+    e0.record()
+    for i in range(reps):
+        sq.sq_probe_stream(xs[i % len(xs)], read_bytes, dst, write_bytes)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    return {"mfma_i8_register_only_tops": mfma_tops, "mfma_i8_frac_of_peak": mfma_tops / INT8_PEAK_TOPS,
+            "stream_encode_mix_gbs": (read_bytes + write_bytes) / (ms * 1e-3) / 1e9,
+            "stream_encode_mix_ms": ms, "stream_read_bytes": read_bytes, "stream_write_bytes": write_bytes,
+            "note": "sq_probe_mfma_i8: 8 independent v_mfma_i32_32x32x32_i8 per wave per iteration, 2 workgroups per CU; "
+                    "sq_probe_stream: coalesced 16-byte reads of X and writes of as many bytes as sq_encode writes"}
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -148,6 +184,14 @@ def main():
         pre = torch.empty(sq.sq_weight_prepack_bytes(p), dtype=torch.uint8, device="cuda")
         sq.sq_weight_prepack(p, wqd, mask, md, pre)
     w = sq.weight(wqd, swd, pre)
+    # Few tokens: the GEMM streams the weights once and is HBM-bound (the ridge of INT8 MFMA against HBM is near
+    # M = 157), so the weights rotate over copies that together exceed the 256 MB Infinity Cache as well.
+    hbm_bound = M <= 128
+    ws = [w]
+    if hbm_bound and not static:
+        n_w = max(2, min(8, -(-300_000_000 // (N * K // 2))))
+        w_copies = [wqd.clone() for _ in range(n_w - 1)]  # sq_weight holds raw addresses: keep the tensors alive
+        ws += [sq.weight(c, swd, None) for c in w_copies]
 
     # Rotating buffers: X copies whose total exceeds the 256 MB Infinity Cache, so the encoder reads HBM.
     x_bytes = M * K * 2
@@ -165,7 +209,7 @@ def main():
         sq.sq_encode(p, xs[i % n_x], a, static_mask=md)
         if ev is not None:
             ev[1].record()
-        sq.sq_gemm(p, a, w, ys[i % n_y], None)
+        sq.sq_gemm(p, a, ws[i % len(ws)], ys[i % n_y], None)
         if ev is not None:
             ev[2].record()
 
@@ -203,15 +247,36 @@ def main():
     enc_s = float(enc_ms.mean()) * 1e-3
     enc_bytes = M * K * 2 + M * K // 2 + M * (K // b) * k + (0 if static else M * K // 8) + 8 * M
     enc_bytes_written_extra = 0 if static else M * K  # the matrix-core-ready image of the high part
+    # what one GEMM launch has to move at least: the encoded activations, the weights, the scales, the output
+    gemm_bytes = (M * K // 2 + M * (K // b) * k + (0 if static else M * K // 8) + 8 * M
+                  + N * K // 2 + 4 * N + 2 * M * N)
 
     traffic, traffic_detail = None, None
     if args.workload in MEASURED_GEMM_TRAFFIC and args.M is None and args.bank is None and args.topk is None:
         traffic_detail = dict(MEASURED_GEMM_TRAFFIC[args.workload])
         traffic = traffic_detail["fetch_bytes"] + traffic_detail["write_bytes"]
-        # what one launch has to move at least: both activation operands, the weights, the scales, the output
         a_bytes = M * K // 2 + (M * (K // b) * k if static else M * K)
         w_bytes = N * K // 2 + (N * (K // b) * k // 2 if static else 0)
         traffic_detail["compulsory_bytes"] = a_bytes + w_bytes + 8 * M + 4 * N + 2 * M * N
+
+    if hbm_bound:
+        roofline = {"kernel": "sq_gemm", "bound": "hbm", "achieved": gemm_bytes / gemm_s / 1e9, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": gemm_bytes / gemm_s / 1e9 / HBM_PEAK_GBS, "traffic": traffic,
+                    "traffic_detail": traffic_detail, "algorithmic_bytes": gemm_bytes,
+                    "weight_buffers_rotated": len(ws)}
+    else:
+        roofline = {"kernel": "sq_gemm", "bound": "mfma", "achieved": alg_ops / gemm_s / 1e12, "peak": INT8_PEAK_TOPS,
+                    "unit": "TOP/s", "frac": alg_ops / gemm_s / 1e12 / INT8_PEAK_TOPS, "traffic": traffic,
+                    "traffic_detail": traffic_detail,
+                    "algorithmic_ops": alg_ops, "issued_mfma_ops": issued_ops,
+                    "issued_frac": issued_ops / gemm_s / 1e12 / INT8_PEAK_TOPS}
+    roofline.update({"ms": gemm_s * 1e3, "ms_median": float(np.median(gemm_ms)), "ms_min": float(gemm_ms.min()),
+                     "effective_tops_2MNK": ops_eff / gemm_s / 1e12})
+
+    # Storage of the encoded activations: as laid out here (low part dense over K) and in the paper's own
+    # accounting of equivalent bits (Section 4.1: the low part counted over its own channels only).
+    storage = {"bytes_per_element_dense_low": 0.5 + k / b + (0.0 if static else 0.125),
+               "equivalent_bits_paper": 8.0 * k / b + 4.0 * (1.0 - k / b)}
 
     out = {
         "metric": "SQ-format linear effective TOPS (encode+GEMM) and % of INT8 MFMA peak, 1 GPU",
@@ -223,19 +288,18 @@ def main():
                    "M": M, "K": K, "N": N, "bank": b, "topk": k, "mode": wl.mode, "out": "bf16",
                    "x_buffers_rotated": n_x},
         "pct_int8_peak_effective": 100.0 * eff_tops / INT8_PEAK_TOPS,
-        "roofline": {"kernel": "sq_gemm", "bound": "mfma", "achieved": alg_ops / gemm_s / 1e12, "peak": INT8_PEAK_TOPS,
-                     "unit": "TOP/s", "frac": alg_ops / gemm_s / 1e12 / INT8_PEAK_TOPS, "traffic": traffic,
-                     "traffic_detail": traffic_detail,
-                     "ms": gemm_s * 1e3, "ms_min": float(gemm_ms.min()),
-                     "algorithmic_ops": alg_ops, "issued_mfma_ops": issued_ops,
-                     "issued_frac": issued_ops / gemm_s / 1e12 / INT8_PEAK_TOPS,
-                     "effective_tops_2MNK": ops_eff / gemm_s / 1e12},
+        "roofline": roofline,
         "encode": {"kernel": "sq_encode", "bound": "hbm", "achieved": enc_bytes / enc_s / 1e9, "peak": HBM_PEAK_GBS,
                    "unit": "GB/s", "frac": enc_bytes / enc_s / 1e9 / HBM_PEAK_GBS, "ms": enc_s * 1e3,
-                   "ms_min": float(enc_ms.min()), "algorithmic_bytes": enc_bytes,
+                   "ms_median": float(np.median(enc_ms)), "ms_min": float(enc_ms.min()),
+                   "algorithmic_bytes": enc_bytes,
                    "extra_bytes_written_hi_dense": enc_bytes_written_extra,
                    "achieved_incl_hi_dense": (enc_bytes + enc_bytes_written_extra) / enc_s / 1e9},
+        "activation_storage": storage,
     }
+
+    if not args.no_probes:
+        out["achievable"] = probes(torch, sq, xs, enc_bytes + enc_bytes_written_extra - M * K * 2)
 
     if not args.no_dense_baseline:
         # Plain per-token W4A8 of the same shape on the same matrix-core kernel (what W4A8 falls back to).

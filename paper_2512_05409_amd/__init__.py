@@ -21,7 +21,7 @@ SQ_OUT_F32, SQ_OUT_BF16 = 0, 1
 EXPORTS = (
     "sq_act_bytes", "sq_gemm_workspace_bytes", "sq_linear_workspace_bytes", "sq_weight_prepack_bytes",
     "sq_weight_prepack", "sq_encode", "sq_gemm", "sq_linear", "sq_dense_w4a8_prepack", "sq_dense_w4a8_gemm",
-    "sq_status_string", "sq_version",
+    "sq_probe_mfma_i8", "sq_probe_stream", "sq_status_string", "sq_version",
 )
 
 
@@ -67,8 +67,10 @@ def lib() -> ctypes.CDLL:
         L.sq_linear.argtypes = [P(sq_params), vp, i64, vp, P(sq_weight), vp, i64, vp, sz, vp]
         L.sq_dense_w4a8_prepack.argtypes = [P(sq_params), vp, vp, vp]
         L.sq_dense_w4a8_gemm.argtypes = [P(sq_params), vp, vp, P(sq_weight), vp, i64, vp]
+        L.sq_probe_mfma_i8.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp]
+        L.sq_probe_stream.argtypes = [vp, sz, vp, sz, vp]
         for f in (L.sq_weight_prepack, L.sq_encode, L.sq_gemm, L.sq_linear, L.sq_dense_w4a8_prepack,
-                  L.sq_dense_w4a8_gemm):
+                  L.sq_dense_w4a8_gemm, L.sq_probe_mfma_i8, L.sq_probe_stream):
             f.restype = ctypes.c_int
         L.sq_status_string.argtypes = [ctypes.c_int]
         L.sq_status_string.restype = ctypes.c_char_p
@@ -205,6 +207,15 @@ def sq_linear(p: sq_params, x_bf16, w: sq_weight, y, workspace, static_mask=None
 
 def sq_dense_w4a8_prepack(p: sq_params, wq, out, stream=None) -> None:
     _check(lib().sq_dense_w4a8_prepack(ctypes.byref(p), _ptr(wq), _ptr(out), _stream(stream)), "sq_dense_w4a8_prepack")
+
+
+def sq_probe_mfma_i8(blocks: int, iters: int, sink, stream=None) -> None:
+    _check(lib().sq_probe_mfma_i8(int(blocks), int(iters), _ptr(sink), _stream(stream)), "sq_probe_mfma_i8")
+
+
+def sq_probe_stream(src, read_bytes: int, dst, write_bytes: int, stream=None) -> None:
+    _check(lib().sq_probe_stream(_ptr(src), int(read_bytes), _ptr(dst), int(write_bytes), _stream(stream)),
+           "sq_probe_stream")
 
 
 def sq_dense_w4a8_gemm(p: sq_params, a_i8, a_scale, w: sq_weight, y, ldy: Optional[int] = None, stream=None) -> None:

@@ -597,6 +597,47 @@ __device__ __forceinline__ void skinny_issue_a(const char* const (&p_lo)[SkinnyC
     __builtin_amdgcn_global_load_lds(p_hi[i] + step * 128, (lds_ptr_t)(dst + C::A_HI + (128 * i + 64 * wave) * 16), 16, 0, 0);
 }
 
+// Operands of one K step of a consumer wave: packed weights of its 32 channels, packed low codes and
+// INT8 high codes of the tokens (two 64-channel halves each).
+template <int TI>
+struct SkinnyOps {
+  v4u fw[2];
+  v4u fa[TI][2];
+  v4i fh[TI][4];
+};
+
+template <int TI>
+__device__ __forceinline__ void skinny_fetch(SkinnyOps<TI>& o, const char* lds, int step, int wave, int r, int h) {
+  typedef SkinnyCfg<TI> C;
+  const char* sa = lds + (step % C::A_STAGES) * C::A_STAGE;
+  const char* sw = lds + C::W_OFF + (step % C::W_STAGES) * C::W_STAGE;
+#pragma unroll
+  for (int gq = 0; gq < 2; ++gq) {
+    o.fw[gq] = *reinterpret_cast<const v4u*>(sw + off4(wave * 32 + r, 2 * gq + h));
+#pragma unroll
+    for (int i = 0; i < TI; ++i) {
+      o.fa[i][gq] = *reinterpret_cast<const v4u*>(sa + C::A_LO + off4(i * 32 + r, 2 * gq + h));
+      o.fh[i][2 * gq] = *reinterpret_cast<const v4i*>(sa + C::A_HI + off8(i * 32 + r, 4 * gq + 2 * h));
+      o.fh[i][2 * gq + 1] = *reinterpret_cast<const v4i*>(sa + C::A_HI + off8(i * 32 + r, 4 * gq + 2 * h + 1));
+    }
+  }
+}
+
+template <int TI>
+__device__ __forceinline__ void skinny_mma(const SkinnyOps<TI>& o, v16i (&acc_lo)[TI], v16i (&acc_hi)[TI]) {
+#pragma unroll
+  for (int gq = 0; gq < 2; ++gq)
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      const v4i bw = widen(o.fw[gq], s2);
+#pragma unroll
+      for (int i = 0; i < TI; ++i) {
+        acc_lo[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(widen(o.fa[i][gq], s2), bw, acc_lo[i], 0, 0, 0);
+        acc_hi[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(o.fh[i][2 * gq + s2], bw, acc_hi[i], 0, 0, 0);
+      }
+    }
+}
+
 template <int TI>
 __global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
   typedef SkinnyCfg<TI> C;
@@ -682,55 +723,38 @@ __global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
   } else {
     pipeline_barrier<0>();
   }
-  // operands of one K step, fetched from LDS one step ahead of the matrix instructions that use them
-  v4u fw[2][2], fa[2][TI][2];
-  v4i fh[2][TI][4];
-#define SQ_SKINNY_FETCH(buf, step)                                                                        \
-  do {                                                                                                    \
-    const char* sa_ = lds + ((step) % C::A_STAGES) * C::A_STAGE;                                          \
-    const char* sw_ = lds + C::W_OFF + ((step) % C::W_STAGES) * C::W_STAGE;                               \
-    _Pragma("unroll") for (int gq = 0; gq < 2; ++gq) {                                                    \
-      fw[buf][gq] = *reinterpret_cast<const v4u*>(sw_ + off4(wave * 32 + r, 2 * gq + h));                 \
-      _Pragma("unroll") for (int i = 0; i < TI; ++i) {                                                    \
-        fa[buf][i][gq] = *reinterpret_cast<const v4u*>(sa_ + C::A_LO + off4(i * 32 + r, 2 * gq + h));     \
-        fh[buf][i][2 * gq] = *reinterpret_cast<const v4i*>(sa_ + C::A_HI + off8(i * 32 + r, 4 * gq + 2 * h));          \
-        fh[buf][i][2 * gq + 1] = *reinterpret_cast<const v4i*>(sa_ + C::A_HI + off8(i * 32 + r, 4 * gq + 2 * h + 1));  \
-      }                                                                                                   \
-    }                                                                                                     \
-  } while (0)
-#define SQ_SKINNY_MMA(buf)                                                                                \
-  do {                                                                                                    \
-    _Pragma("unroll") for (int gq = 0; gq < 2; ++gq) _Pragma("unroll") for (int s2 = 0; s2 < 2; ++s2) {   \
-      const v4i bw_ = widen(fw[buf][gq], s2);                                                             \
-      _Pragma("unroll") for (int i = 0; i < TI; ++i) {                                                    \
-        acc_lo[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(widen(fa[buf][i][gq], s2), bw_, acc_lo[i], 0, 0, 0);  \
-        acc_hi[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fh[buf][i][2 * gq + s2], bw_, acc_hi[i], 0, 0, 0);    \
-      }                                                                                                   \
-    }                                                                                                     \
-  } while (0)
-  SQ_SKINNY_FETCH(0, 0);
-  for (int kt = 0; kt < steps; kt += 2) {  // two steps per trip: the operand buffers alternate statically
-    if (kt + 1 < steps) SQ_SKINNY_FETCH(1, kt + 1);
-    if (kt + 3 < steps) {
-      const int ahead = kt + 3;
-      skinny_issue_a<TI>(p_lo, p_hi, lds, ahead, wave);
-    }
-    SQ_SKINNY_MMA(0);
+  // Operands of one K step are fetched from LDS one step ahead of the matrix instructions that use them.
+  // The steady state takes two steps per trip (the operand sets alternate statically) and has no
+  // branches, so that the compiler keeps the accumulators where they are and waits for the LDS reads of
+  // step kt+1 only after the matrix instructions of step kt have been issued.
+  SkinnyOps<TI> o0, o1;
+  skinny_fetch<TI>(o0, lds, 0, wave, r, h);
+  int kt = 0;
+  for (; kt + 4 < steps; kt += 2) {
+    skinny_fetch<TI>(o1, lds, kt + 1, wave, r, h);
+    skinny_issue_a<TI>(p_lo, p_hi, lds, kt + 3, wave);
+    skinny_mma<TI>(o0, acc_lo, acc_hi);
+    pipeline_barrier<C::NA>();
+    skinny_fetch<TI>(o0, lds, kt + 2, wave, r, h);
+    skinny_issue_a<TI>(p_lo, p_hi, lds, kt + 4, wave);
+    skinny_mma<TI>(o1, acc_lo, acc_hi);
+    pipeline_barrier<C::NA>();
+  }
+  // the last (at most four) steps: nothing or little left to copy
+  while (kt < steps) {
+    if (kt + 1 < steps) skinny_fetch<TI>(o1, lds, kt + 1, wave, r, h);
+    if (kt + 3 < steps) skinny_issue_a<TI>(p_lo, p_hi, lds, kt + 3, wave);
+    skinny_mma<TI>(o0, acc_lo, acc_hi);
     if (kt + 3 < steps) pipeline_barrier<C::NA>();
     else pipeline_barrier<0>();
-    if (kt + 1 < steps) {
-      if (kt + 2 < steps) SQ_SKINNY_FETCH(0, kt + 2);
-      if (kt + 4 < steps) {
-        const int ahead = kt + 4;
-        skinny_issue_a<TI>(p_lo, p_hi, lds, ahead, wave);
-      }
-      SQ_SKINNY_MMA(1);
-      if (kt + 4 < steps) pipeline_barrier<C::NA>();
-      else pipeline_barrier<0>();
-    }
+    if (++kt >= steps) break;
+    if (kt + 1 < steps) skinny_fetch<TI>(o0, lds, kt + 1, wave, r, h);
+    if (kt + 3 < steps) skinny_issue_a<TI>(p_lo, p_hi, lds, kt + 3, wave);
+    skinny_mma<TI>(o1, acc_lo, acc_hi);
+    if (kt + 3 < steps) pipeline_barrier<C::NA>();
+    else pipeline_barrier<0>();
+    ++kt;
   }
-#undef SQ_SKINNY_FETCH
-#undef SQ_SKINNY_MMA
 
   // epilogue: the outputs are few (M <= 64 rows); plain stores
   if (n < g.N) {

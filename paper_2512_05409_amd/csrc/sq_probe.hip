@@ -1,0 +1,67 @@
+// Two measurement probes behind the C ABI (sq_probe_mfma_i8, sq_probe_stream): what this chip sustains
+// on the matrix instruction the products use and on a plain streaming kernel with a chosen mix of
+// bytes read and written.  The benchmark prints them beside the vendor peaks; nothing on the layer's
+// path calls them.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sq.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
+// Every wave issues iters x 8 independent v_mfma_i32_32x32x32_i8 on register operands.
+__global__ __launch_bounds__(256) void mfma_rate_kernel(int iters, int32_t* __restrict__ sink) {
+  v4i a = {static_cast<int>(threadIdx.x), 1, 2, 3}, b = {4, 5, 6, static_cast<int>(threadIdx.x)};
+  v16i acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+  }
+  int s = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+// Reads n_read 16-byte chunks and writes n_write chunks, both coalesced, grid-stride.
+__global__ __launch_bounds__(256) void stream_kernel(const v4u* __restrict__ src, int64_t n_read, v4u* __restrict__ dst,
+                                                     int64_t n_write) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  const int64_t t = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  v4u acc = {0u, 0u, 0u, 0u};
+  for (int64_t i = t; i < n_read; i += stride) acc ^= src[i];
+  for (int64_t i = t; i < n_write; i += stride) dst[i] = acc;
+}
+
+}  // namespace
+
+extern "C" int sq_probe_mfma_i8(int blocks, int iters, int32_t* sink, void* stream) {
+  if (!sink) return SQ_ERR_NULL;
+  if (blocks <= 0 || blocks > 65536 || iters <= 0) return SQ_ERR_SHAPE;
+  hipLaunchKernelGGL(mfma_rate_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), iters, sink);
+  return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+extern "C" int sq_probe_stream(const void* src, size_t read_bytes, void* dst, size_t write_bytes, void* stream) {
+  if ((read_bytes && !src) || (write_bytes && !dst)) return SQ_ERR_NULL;
+  if ((read_bytes | write_bytes) & 15) return SQ_ERR_SHAPE;
+  if (read_bytes + write_bytes == 0) return SQ_ERR_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15) return SQ_ERR_ALIGN;
+  const int64_t n_read = static_cast<int64_t>(read_bytes / 16), n_write = static_cast<int64_t>(write_bytes / 16);
+  const int64_t most = n_read > n_write ? n_read : n_write;
+  int64_t blocks = (most + 255) / 256;
+  if (blocks > 256 * 32) blocks = 256 * 32;  // a few chunks per thread at the benchmark's sizes
+  hipLaunchKernelGGL(stream_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const v4u*>(src), n_read, static_cast<v4u*>(dst), n_write);
+  return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}

@@ -112,6 +112,18 @@ def test_null_alignment_and_leading_dimension(L):
     assert L.sq_dense_w4a8_gemm(ctypes.byref(p), FAKE, FAKE, ctypes.byref(w), FAKE, 512, None) == -1  # needs prepacked
 
 
+def test_probe_arguments(L):
+    assert L.sq_probe_mfma_i8(4, 10, None, None) == -1
+    assert L.sq_probe_mfma_i8(0, 10, FAKE, None) == -2
+    assert L.sq_probe_mfma_i8(4, 0, FAKE, None) == -2
+    assert L.sq_probe_mfma_i8(1 << 20, 1, FAKE, None) == -2
+    assert L.sq_probe_stream(None, 1024, FAKE, 1024, None) == -1
+    assert L.sq_probe_stream(FAKE, 1024, None, 1024, None) == -1
+    assert L.sq_probe_stream(FAKE, 1000, FAKE, 1024, None) == -2
+    assert L.sq_probe_stream(FAKE, 0, FAKE, 0, None) == -2
+    assert L.sq_probe_stream(FAKE + 4, 1024, FAKE, 1024, None) == -4
+
+
 def test_prepack_checks_the_mask_on_the_host(L):
     ps = sq.params(16, 512, 512, 64, 8, mode=1)
     good = np.zeros(512 // 32, np.uint32)
