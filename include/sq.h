@@ -147,6 +147,25 @@ int sq_dense_w4a8_prepack(const sq_params *p, const uint8_t *wq, void *out, void
 int sq_dense_w4a8_gemm(const sq_params *p, const int8_t *a_i8, const float *a_scale, const sq_weight *w,
                        void *y, int64_t ldy, void *stream);
 
+/* Static-mask calibration on the device (Algorithm 2 up to the mask; Section 3.2.2):
+ *   Abar_j = mean over the T calibration tokens of |x_calib[t, j]|,
+ *   I_j    = | Abar_j * sum_n scale[n] * wq[n, j] |   (the dequantised weights of the layer),
+ * and in every bank the topk channels of largest I_j are the high-precision ones, ties to the lower
+ * channel.  All arithmetic is fp64; the sums are formed as partial sums over fixed chunks of rows,
+ * added in chunk order, so a call gives the same bits every time.
+ * p: K, N, bank, topk are read, mode must be SQ_STATIC.  x_calib device bf16 [T, ldx] (ldx >= K,
+ * multiple of 8, 16-byte aligned), w->wq / w->scale as for sq_gemm (w->prepacked is not read).
+ * mask_out device [K/32] uint32 (bit j%32 of word j/32 set <=> channel j is high): the static_mask
+ * argument of sq_encode / sq_linear and, copied to the host, of sq_weight_prepack.
+ * importance_out device [K] doubles, or NULL.  workspace device, 16-byte aligned,
+ * sq_calibrate_workspace_bytes(p, T) bytes (0 for invalid arguments); the caller owns everything.
+ * Errors: SQ_ERR_NULL, SQ_ERR_SHAPE (T <= 0 or > 2^24, ldx < K), SQ_ERR_UNSUPPORTED (dynamic mode),
+ * SQ_ERR_ALIGN, SQ_ERR_WORKSPACE, SQ_ERR_LAUNCH.  Only enqueues work on `stream`. */
+size_t sq_calibrate_workspace_bytes(const sq_params *p, int64_t T);
+int sq_calibrate_static(const sq_params *p, const uint16_t *x_calib, int64_t ldx, int64_t T, const sq_weight *w,
+                        uint32_t *mask_out, double *importance_out, void *workspace, size_t workspace_bytes,
+                        void *stream);
+
 /* Measurement probes (used by the benchmark only; nothing on the layer's path calls them).
  * sq_probe_mfma_i8: `blocks` workgroups of 4 waves, each wave issuing iters x 8 independent
  *   v_mfma_i32_32x32x32_i8 (the instruction both products of Section 3.3 run on here) on register

@@ -21,7 +21,7 @@ SQ_OUT_F32, SQ_OUT_BF16 = 0, 1
 EXPORTS = (
     "sq_act_bytes", "sq_gemm_workspace_bytes", "sq_linear_workspace_bytes", "sq_weight_prepack_bytes",
     "sq_weight_prepack", "sq_encode", "sq_gemm", "sq_linear", "sq_dense_w4a8_prepack", "sq_dense_w4a8_gemm",
-    "sq_probe_mfma_i8", "sq_probe_stream", "sq_status_string", "sq_version",
+    "sq_calibrate_workspace_bytes", "sq_calibrate_static", "sq_probe_mfma_i8", "sq_probe_stream", "sq_status_string", "sq_version",
 )
 
 
@@ -67,6 +67,10 @@ def lib() -> ctypes.CDLL:
         L.sq_linear.argtypes = [P(sq_params), vp, i64, vp, P(sq_weight), vp, i64, vp, sz, vp]
         L.sq_dense_w4a8_prepack.argtypes = [P(sq_params), vp, vp, vp]
         L.sq_dense_w4a8_gemm.argtypes = [P(sq_params), vp, vp, P(sq_weight), vp, i64, vp]
+        L.sq_calibrate_workspace_bytes.argtypes = [P(sq_params), i64]
+        L.sq_calibrate_workspace_bytes.restype = sz
+        L.sq_calibrate_static.argtypes = [P(sq_params), vp, i64, i64, P(sq_weight), vp, vp, vp, sz, vp]
+        L.sq_calibrate_static.restype = ctypes.c_int
         L.sq_probe_mfma_i8.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp]
         L.sq_probe_stream.argtypes = [vp, sz, vp, sz, vp]
         for f in (L.sq_weight_prepack, L.sq_encode, L.sq_gemm, L.sq_linear, L.sq_dense_w4a8_prepack,
@@ -207,6 +211,18 @@ def sq_linear(p: sq_params, x_bf16, w: sq_weight, y, workspace, static_mask=None
 
 def sq_dense_w4a8_prepack(p: sq_params, wq, out, stream=None) -> None:
     _check(lib().sq_dense_w4a8_prepack(ctypes.byref(p), _ptr(wq), _ptr(out), _stream(stream)), "sq_dense_w4a8_prepack")
+
+
+def sq_calibrate_workspace_bytes(p: sq_params, T: int) -> int:
+    return int(lib().sq_calibrate_workspace_bytes(ctypes.byref(p), int(T)))
+
+
+def sq_calibrate_static(p: sq_params, x_calib, T: int, w: sq_weight, mask_out, importance_out, workspace,
+                        ldx: Optional[int] = None, stream=None) -> None:
+    _check(lib().sq_calibrate_static(ctypes.byref(p), _ptr(x_calib), p.K if ldx is None else ldx, int(T),
+                                     ctypes.byref(w), _ptr(mask_out), _ptr(importance_out), _ptr(workspace),
+                                     0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                     _stream(stream)), "sq_calibrate_static")
 
 
 def sq_probe_mfma_i8(blocks: int, iters: int, sink, stream=None) -> None:

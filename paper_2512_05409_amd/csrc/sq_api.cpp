@@ -115,6 +115,36 @@ int sq_weight_prepack(const sq_params* p, const uint8_t* wq, const uint32_t* sta
                                    static_cast<uint8_t*>(out), static_cast<hipStream_t>(stream));
 }
 
+size_t sq_calibrate_workspace_bytes(const sq_params* p, int64_t T) {
+  if (check_params(p) != SQ_OK || p->mode != SQ_STATIC || T <= 0 || T > (1 << 24)) return 0;
+  int ca, ra, cw, rw;
+  sq::calibrate_chunks(T, p->N, &ca, &ra, &cw, &rw);
+  return (static_cast<size_t>(ca) + cw + 1) * p->K * sizeof(double);
+}
+
+int sq_calibrate_static(const sq_params* p, const uint16_t* x_calib, int64_t ldx, int64_t T, const sq_weight* w,
+                        uint32_t* mask_out, double* importance_out, void* workspace, size_t workspace_bytes,
+                        void* stream) {
+  int rc = check_params(p);
+  if (rc != SQ_OK) return rc;
+  if (p->mode != SQ_STATIC) return SQ_ERR_UNSUPPORTED;
+  if (!x_calib || !w || !w->wq || !w->scale || !mask_out) return SQ_ERR_NULL;
+  if (T <= 0 || T > (1 << 24) || ldx < p->K) return SQ_ERR_SHAPE;
+  if (!aligned16(x_calib) || (ldx % 8) || !aligned16(w->wq) || !aligned16(w->scale) || !aligned16(mask_out) ||
+      !aligned16(importance_out))
+    return SQ_ERR_ALIGN;
+  const size_t need = sq_calibrate_workspace_bytes(p, T);
+  if (!workspace || workspace_bytes < need) return SQ_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return SQ_ERR_ALIGN;
+  int ca, ra, cw, rw;
+  sq::calibrate_chunks(T, p->N, &ca, &ra, &cw, &rw);
+  double* pa = static_cast<double*>(workspace);
+  double* pw = pa + static_cast<size_t>(ca) * p->K;
+  double* imp = importance_out ? importance_out : pw + static_cast<size_t>(cw) * p->K;
+  return sq::launch_calibrate_static(*p, x_calib, ldx, T, w->wq, w->scale, mask_out, imp, pa, pw,
+                                     static_cast<hipStream_t>(stream));
+}
+
 int sq_encode(const sq_params* p, const uint16_t* x_bf16, int64_t ldx, const uint32_t* static_mask, const sq_act* out,
               void* stream) {
   int rc = check_params(p);

@@ -23,6 +23,13 @@ int launch_expand_hi(const sq_params& p, const sq_act& a, int8_t* s_hi_dense, hi
 int launch_weight_prepack(int N, int K, int bank, int topk, int k_hi_padded, const uint8_t* wq, const uint32_t* mask,
                           uint8_t* out, hipStream_t st);
 
+// Static-mask calibration (Algorithm 2): how the rows are chunked, and the four kernels.
+// partial_a: [chunks_a, K] doubles, partial_w: [chunks_w, K] doubles, importance: [K] doubles.
+void calibrate_chunks(int64_t T, int N, int* chunks_a, int* rows_a, int* chunks_w, int* rows_w);
+int launch_calibrate_static(const sq_params& p, const uint16_t* x, int64_t ldx, int64_t T, const uint8_t* wq,
+                            const float* s_w, uint32_t* mask, double* importance, double* partial_a, double* partial_w,
+                            hipStream_t st);
+
 struct GemmArgs {
   int M, N, K;          // K of the low / full pass
   int K_hi;             // channels of the compact high pass (static / dense-W4A8), multiple of 32

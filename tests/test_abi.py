@@ -112,6 +112,29 @@ def test_null_alignment_and_leading_dimension(L):
     assert L.sq_dense_w4a8_gemm(ctypes.byref(p), FAKE, FAKE, ctypes.byref(w), FAKE, 512, None) == -1  # needs prepacked
 
 
+def test_calibrate_arguments(L):
+    ps = sq.params(1, 512, 64, 64, 8, mode=1)
+    pd = sq.params(1, 512, 64, 64, 8, mode=0)
+    w = sq.sq_weight(FAKE, FAKE, None)
+    need = L.sq_calibrate_workspace_bytes(ctypes.byref(ps), 100)
+    assert need >= (2 + 1) * 512 * 8 and need % 8 == 0
+    assert L.sq_calibrate_workspace_bytes(ctypes.byref(pd), 100) == 0   # dynamic mode has no mask to calibrate
+    assert L.sq_calibrate_workspace_bytes(ctypes.byref(ps), 0) == 0
+    call = lambda p, x=FAKE, ldx=512, T=100, wt=w, m=FAKE, imp=None, ws=FAKE, nb=need: L.sq_calibrate_static(
+        ctypes.byref(p), x, ldx, T, ctypes.byref(wt), m, imp, ws, nb, None)
+    assert call(pd) == -3
+    assert call(ps, x=None) == -1
+    assert call(ps, m=None) == -1
+    assert call(ps, wt=sq.sq_weight(None, FAKE, None)) == -1
+    assert call(ps, T=0) == -2
+    assert call(ps, ldx=256) == -2
+    assert call(ps, ldx=516) == -4
+    assert call(ps, x=FAKE + 2) == -4
+    assert call(ps, imp=FAKE + 8) == -4
+    assert call(ps, ws=None) == -7
+    assert call(ps, nb=need - 1) == -7
+
+
 def test_probe_arguments(L):
     assert L.sq_probe_mfma_i8(4, 10, None, None) == -1
     assert L.sq_probe_mfma_i8(0, 10, FAKE, None) == -2

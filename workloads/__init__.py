@@ -28,7 +28,6 @@ __all__ = [
     "bf16_bits_to_f32",
     "pack_int4",
     "unpack_int4",
-    "drawn_static_mask",
 ]
 
 
@@ -192,21 +191,3 @@ def make(
         name=name, M=m, K=k, N=n, bank=b, topk=tk, mode=mode, x_bits=x_bits,
         wq_packed=wq, w_scale=ws, outlier_channels=chans, calib_bits=calib, seed=seed,
     )
-
-
-def drawn_static_mask(wl: Workload, seed: int = 7) -> np.ndarray:
-    """A channel mask [K/32] uint32 with exactly ``topk`` bits per bank, drawn rather than calibrated:
-    the workload's outlier channels first (at most topk per bank), the rest of each bank's quota filled
-    with seeded random channels.  It stands in for a calibrated mask where only the shape of the work
-    matters (timing); parity tests use the oracle's calibrator instead."""
-    rng = np.random.Generator(np.random.PCG64([wl.seed, seed]))
-    flags = np.zeros(wl.K, dtype=bool)
-    for g in range(wl.K // wl.bank):
-        lo, hi = g * wl.bank, (g + 1) * wl.bank
-        out = [int(c) for c in wl.outlier_channels if lo <= c < hi][: wl.topk]
-        flags[out] = True
-        rest = np.array([c for c in range(lo, hi) if not flags[c]])
-        fill = rng.choice(rest, size=wl.topk - len(out), replace=False)
-        flags[fill] = True
-    words = flags.reshape(-1, 32).astype(np.uint32) << np.arange(32, dtype=np.uint32)[None, :]
-    return np.bitwise_or.reduce(words, axis=1).astype(np.uint32)
