@@ -545,8 +545,8 @@ int launch_mode(const GemmArgs& g, hipStream_t st) {
 // Vector-memory operations of a wave retire in order, so one wave cannot keep a deep queue of weight
 // loads and, at the same time, wait for the shallow queue of (L2-resident) activation loads.  The
 // workgroup is therefore specialised: waves 0 and 1 multiply (32 output channels each, all tokens)
-// and copy the activation tiles three K steps ahead; wave 2 only copies weights, seven K steps ahead,
-// into its own ring of eight LDS stages.  Each wave waits on its own counter; one workgroup barrier
+// and copy the activation tiles six K steps ahead (ring of eight stages); wave 2 only copies weights,
+// seven K steps ahead, into its own ring of eight LDS stages.  Each wave waits on its own counter; one workgroup barrier
 // per K step publishes both copies.  Both copies are published one step earlier than they are
 // multiplied, so that a consumer fetches the operands of step kt+1 from LDS while the matrix
 // instructions of step kt run: the per-step chain "barrier -> LDS read -> multiply -> barrier", which
@@ -560,7 +560,8 @@ struct SkinnyCfg {
   static constexpr int A_LO = 0;
   static constexpr int A_HI = BM * 64;
   static constexpr int A_STAGE = BM * 192;
-  static constexpr int A_STAGES = 4;
+  static constexpr int A_STAGES = 8;
+  static constexpr int A_DIST = 6;  // the activation copy of step kt + A_DIST is enqueued during step kt
   static constexpr int W_OFF = A_STAGES * A_STAGE;
   static constexpr int W_STAGE = BN * 64;
   static constexpr int W_STAGES = 8;
@@ -606,11 +607,14 @@ struct SkinnyOps {
   v4i fh[TI][4];
 };
 
+// sa_idx / sw_idx: ring stages of the step's activation and weight tiles (compile-time constants in the
+// steady state, so that the reads differ only in their immediate offsets).
 template <int TI>
-__device__ __forceinline__ void skinny_fetch(SkinnyOps<TI>& o, const char* lds, int step, int wave, int r, int h) {
+__device__ __forceinline__ void skinny_fetch_at(SkinnyOps<TI>& o, const char* lds, int sa_idx, int sw_idx, int wave,
+                                                int r, int h) {
   typedef SkinnyCfg<TI> C;
-  const char* sa = lds + (step % C::A_STAGES) * C::A_STAGE;
-  const char* sw = lds + C::W_OFF + (step % C::W_STAGES) * C::W_STAGE;
+  const char* sa = lds + sa_idx * C::A_STAGE;
+  const char* sw = lds + C::W_OFF + sw_idx * C::W_STAGE;
 #pragma unroll
   for (int gq = 0; gq < 2; ++gq) {
     o.fw[gq] = *reinterpret_cast<const v4u*>(sw + off4(wave * 32 + r, 2 * gq + h));
@@ -621,6 +625,11 @@ __device__ __forceinline__ void skinny_fetch(SkinnyOps<TI>& o, const char* lds, 
       o.fh[i][2 * gq + 1] = *reinterpret_cast<const v4i*>(sa + C::A_HI + off8(i * 32 + r, 4 * gq + 2 * h + 1));
     }
   }
+}
+
+template <int TI>
+__device__ __forceinline__ void skinny_fetch(SkinnyOps<TI>& o, const char* lds, int step, int wave, int r, int h) {
+  skinny_fetch_at<TI>(o, lds, step % SkinnyCfg<TI>::A_STAGES, step % SkinnyCfg<TI>::W_STAGES, wave, r, h);
 }
 
 template <int TI>
@@ -636,6 +645,43 @@ __device__ __forceinline__ void skinny_mma(const SkinnyOps<TI>& o, v16i (&acc_lo
         acc_hi[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(o.fh[i][2 * gq + s2], bw, acc_hi[i], 0, 0, 0);
       }
     }
+}
+
+// Multiply one step, then join the step's barrier; `copied`: this step enqueued an activation copy, so
+// A_DIST - 2 younger ones may stay in flight, otherwise everything outstanding is waited for.
+template <int TI>
+__device__ __forceinline__ void pipeline_barrier_after(const SkinnyOps<TI>& cur, v16i (&acc_lo)[TI], v16i (&acc_hi)[TI],
+                                                       bool copied) {
+  typedef SkinnyCfg<TI> C;
+  skinny_mma<TI>(cur, acc_lo, acc_hi);
+  if (copied) pipeline_barrier<(C::A_DIST - 2) * C::NA>();
+  else pipeline_barrier<0>();
+}
+
+// Step kt + U of a trip of eight steps that starts at a multiple of eight (the ring sizes divide eight, so
+// every stage index is a compile-time constant).  The sources of the activation copies of step kt + U + A_DIST
+// are a wave-uniform base (scalar registers, advanced by scalar additions) plus a per-lane 32-bit offset
+// that never changes.  (The instruction's immediate offset is no use here: for a copy into LDS it is added
+// to the LDS address as well.)
+template <int TI, int U>
+__device__ __forceinline__ void skinny_steady_step(const SkinnyOps<TI>& cur, SkinnyOps<TI>& nxt, const char* ub_lo,
+                                                   const char* ub_hi, const unsigned (&l_lo)[SkinnyCfg<TI>::N_LO],
+                                                   const unsigned (&l_hi)[SkinnyCfg<TI>::N_HI], char* lds, int wave,
+                                                   int r, int h, v16i (&acc_lo)[TI], v16i (&acc_hi)[TI]) {
+  typedef SkinnyCfg<TI> C;
+  static_assert(8 % C::A_STAGES == 0 && 8 % C::W_STAGES == 0, "ring sizes must divide the trip length");
+  skinny_fetch_at<TI>(nxt, lds, (U + 1) % C::A_STAGES, (U + 1) % C::W_STAGES, wave, r, h);
+  char* dst = lds + ((U + C::A_DIST) % C::A_STAGES) * C::A_STAGE;
+  const char* s_lo = ub_lo + (U + C::A_DIST) * 64;
+  const char* s_hi = ub_hi + (U + C::A_DIST) * 128;
+#pragma unroll
+  for (int i = 0; i < C::N_LO; ++i)
+    __builtin_amdgcn_global_load_lds(s_lo + l_lo[i], (lds_ptr_t)(dst + C::A_LO + (128 * i + 64 * wave) * 16), 16, 0, 0);
+#pragma unroll
+  for (int i = 0; i < C::N_HI; ++i)
+    __builtin_amdgcn_global_load_lds(s_hi + l_hi[i], (lds_ptr_t)(dst + C::A_HI + (128 * i + 64 * wave) * 16), 16, 0, 0);
+  skinny_mma<TI>(cur, acc_lo, acc_hi);
+  pipeline_barrier<(C::A_DIST - 2) * C::NA>();  // the copies of steps <= kt + U + 2 have landed
 }
 
 template <int TI>
@@ -714,45 +760,62 @@ __global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
       acc_hi[i][q] = 0;
     }
 
-  // at barrier kt (prologue: kt = -1) this wave's activation copies of steps <= kt+2 have landed
-  skinny_issue_a<TI>(p_lo, p_hi, lds, 0, wave);
-  if (steps > 1) skinny_issue_a<TI>(p_lo, p_hi, lds, 1, wave);
-  if (steps > 2) {
-    skinny_issue_a<TI>(p_lo, p_hi, lds, 2, wave);
-    pipeline_barrier<C::NA>();
-  } else {
-    pipeline_barrier<0>();
-  }
+  // At barrier kt (prologue: kt = -1) this wave's activation copies of steps <= kt+2 have landed.  A copy
+  // is enqueued A_DIST steps before it is multiplied and has A_DIST - 2 steps to arrive: with one step
+  // (a few hundred nanoseconds here) the wait for it was half of every step.
+  constexpr int D = C::A_DIST;
+#pragma unroll
+  for (int s0 = 0; s0 < D; ++s0)
+    if (s0 < steps) skinny_issue_a<TI>(p_lo, p_hi, lds, s0, wave);
+  if (steps >= D) pipeline_barrier<(D - 2) * C::NA>();
+  else pipeline_barrier<0>();
   // Operands of one K step are fetched from LDS one step ahead of the matrix instructions that use them.
-  // The steady state takes two steps per trip (the operand sets alternate statically) and has no
-  // branches, so that the compiler keeps the accumulators where they are and waits for the LDS reads of
-  // step kt+1 only after the matrix instructions of step kt have been issued.
+  // The steady state has no branches (the compiler then keeps the accumulators where they are and waits
+  // for the LDS reads of step kt+1 only after the matrix instructions of step kt have been issued) and no
+  // address arithmetic: with few tokens a step is a handful of matrix instructions, so every other
+  // instruction in it counts.
   SkinnyOps<TI> o0, o1;
   skinny_fetch<TI>(o0, lds, 0, wave, r, h);
   int kt = 0;
-  for (; kt + 4 < steps; kt += 2) {
-    skinny_fetch<TI>(o1, lds, kt + 1, wave, r, h);
-    skinny_issue_a<TI>(p_lo, p_hi, lds, kt + 3, wave);
-    skinny_mma<TI>(o0, acc_lo, acc_hi);
-    pipeline_barrier<C::NA>();
-    skinny_fetch<TI>(o0, lds, kt + 2, wave, r, h);
-    skinny_issue_a<TI>(p_lo, p_hi, lds, kt + 4, wave);
-    skinny_mma<TI>(o1, acc_lo, acc_hi);
-    pipeline_barrier<C::NA>();
+  {
+    // steady state: trips of eight steps with compile-time stage indices
+    unsigned l_lo[C::N_LO], l_hi[C::N_HI];  // per-lane byte offsets of the copies' sources (below 2^32: M <= 64 rows)
+#pragma unroll
+    for (int i = 0; i < C::N_LO; ++i) l_lo[i] = static_cast<unsigned>(p_lo[i] - reinterpret_cast<const char*>(g.a_lo));
+#pragma unroll
+    for (int i = 0; i < C::N_HI; ++i) l_hi[i] = static_cast<unsigned>(p_hi[i] - reinterpret_cast<const char*>(g.a_hi_dense));
+    const char* ub_lo = reinterpret_cast<const char*>(g.a_lo);
+    const char* ub_hi = reinterpret_cast<const char*>(g.a_hi_dense);
+    for (; kt + 8 + D <= steps; kt += 8) {  // the copy of step kt + 7 + A_DIST is the last one a trip enqueues
+      skinny_steady_step<TI, 0>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, 1>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, 2>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, 3>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, 4>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, 5>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, 6>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, 7>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      ub_lo += 8 * 64;
+      ub_hi += 8 * 128;
+    }
   }
-  // the last (at most four) steps: nothing or little left to copy
+  // the remaining steps (fewer than 8 + A_DIST): stage indices and addresses computed at run time
   while (kt < steps) {
     if (kt + 1 < steps) skinny_fetch<TI>(o1, lds, kt + 1, wave, r, h);
-    if (kt + 3 < steps) skinny_issue_a<TI>(p_lo, p_hi, lds, kt + 3, wave);
-    skinny_mma<TI>(o0, acc_lo, acc_hi);
-    if (kt + 3 < steps) pipeline_barrier<C::NA>();
-    else pipeline_barrier<0>();
+    if (kt + D < steps) {
+      skinny_issue_a<TI>(p_lo, p_hi, lds, kt + D, wave);
+      pipeline_barrier_after<TI>(o0, acc_lo, acc_hi, true);
+    } else {
+      pipeline_barrier_after<TI>(o0, acc_lo, acc_hi, false);
+    }
     if (++kt >= steps) break;
     if (kt + 1 < steps) skinny_fetch<TI>(o0, lds, kt + 1, wave, r, h);
-    if (kt + 3 < steps) skinny_issue_a<TI>(p_lo, p_hi, lds, kt + 3, wave);
-    skinny_mma<TI>(o1, acc_lo, acc_hi);
-    if (kt + 3 < steps) pipeline_barrier<C::NA>();
-    else pipeline_barrier<0>();
+    if (kt + D < steps) {
+      skinny_issue_a<TI>(p_lo, p_hi, lds, kt + D, wave);
+      pipeline_barrier_after<TI>(o1, acc_lo, acc_hi, true);
+    } else {
+      pipeline_barrier_after<TI>(o1, acc_lo, acc_hi, false);
+    }
     ++kt;
   }
 

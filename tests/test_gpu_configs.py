@@ -86,7 +86,7 @@ def test_config2_qkv7b():
     run_config(workloads.make("c2_qkv7b"), n_rows=12)
 
 
-@pytest.mark.parametrize("bank,topk", [(64, 8), (32, 2), (32, 8), (64, 4), (64, 16), (128, 8), (128, 32)])
+@pytest.mark.parametrize("bank,topk", [(64, 8), (32, 2), (32, 4), (32, 8), (64, 4), (64, 16), (128, 8), (128, 16), (128, 32)])
 def test_config3_mlp7b(bank, topk):
     _say(f"config 3 bank={bank} topk={topk}")
     # the (b, k) sweep reuses the shape with a reduced N except for the headline setting
