@@ -71,6 +71,15 @@ def test_encode_dynamic_shapes(M, K, bank, topk):
     assert_encoding_equal(act, oracle.encode(bits, bank, topk))
 
 
+@pytest.mark.parametrize("K,bank,topk", [(32768, 64, 8), (65536, 128, 16), (16384, 32, 4)])
+def test_encode_dynamic_longest_rows(K, bank, topk):
+    """K / bank = 512 banks per row: the most the encoder takes (one workgroup of 512 lanes per row)."""
+    _say(f"encode dynamic longest row K={K} bank={bank}")
+    bits, _, _ = random_case(K + bank, M=5, K=K, N=8, outliers=40)
+    p, act = run_encode(bits, bank, topk)
+    assert_encoding_equal(act, oracle.encode(bits, bank, topk))
+
+
 def test_encode_leading_dimension_and_determinism():
     _say("encode ldx / determinism")
     bits, _, _ = random_case(5, M=20, K=512, N=8)
@@ -166,6 +175,26 @@ def test_gemm_extreme_codes_do_not_overflow():
     p = sq.params(M, K, N, bank, topk, out_dtype=sq.SQ_OUT_F32)
     y, alo, ahi = run_gemm(p, enc, wq, sw, sq.SQ_OUT_F32)
     assert np.array_equal(alo, prod.acc_lo) and np.array_equal(ahi, prod.acc_hi)
+
+
+def test_gemm_largest_k_extreme_codes():
+    """K = 65536 with bank 128 (the longest row the encoder takes), every code at its extreme: the widened
+    accumulators reach 7*8*K*3/4*256 = 7.0e8 and 127*8*K/4*16 = 2.7e8, inside INT32."""
+    _say("gemm largest K")
+    M, K, N, bank, topk = 3, 65536, 40, 128, 32
+    x = np.full((M, K), 1.0, np.float32)
+    x[:, ::4] = 64.0
+    x[1] *= -1
+    bits = f32_to_bf16_bits(x)
+    wq = pack_int4(np.full((N, K), -8, np.int8))
+    sw = np.full(N, 0.01, np.float32)
+    enc = oracle.encode(bits, bank, topk)
+    prod = oracle.gemm(enc, wq, sw)
+    assert abs(int(prod.acc_lo[0, 0])) == 7 * 8 * (K * 3 // 4) and abs(int(prod.acc_hi[0, 0])) == 127 * 8 * (K // 4)
+    p = sq.params(M, K, N, bank, topk, out_dtype=sq.SQ_OUT_F32)
+    y, alo, ahi = run_gemm(p, enc, wq, sw, sq.SQ_OUT_F32)
+    assert np.array_equal(alo, prod.acc_lo) and np.array_equal(ahi, prod.acc_hi)
+    assert np.array_equal(y.view(np.uint32), prod.y32.view(np.uint32))
 
 
 @pytest.mark.parametrize("M,K,N,bank,topk", [(16, 512, 512, 64, 8), (150, 1024, 200, 32, 4), (40, 11008, 64, 64, 8)])
