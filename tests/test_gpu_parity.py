@@ -137,12 +137,16 @@ def run_gemm(p, enc_host, wq, sw, out_dtype, prepacked=None, static_mask=None):
 
 
 # shapes chosen to reach every kernel variant: the 128x256 tile (M > 64), the 64x64 tile (32 < M <= 64, or
-# M <= 32 with K % 128 != 0), the weight-streaming kernel (M <= 32, K % 128 == 0), ragged M / N / K edges,
-# and more K steps than the loader's ring of eight stages
+# M <= 32 with K % 128 != 0), the weight-streaming kernel (M <= 32, K % 128 == 0) with 1 ... 26 K steps
+# (fewer than its rings hold, exactly as many, the first trip of the steady state, several tail lengths),
+# ragged M / N / K edges
 @pytest.mark.parametrize("M,K,N,bank,topk", [(16, 512, 512, 64, 8), (200, 1024, 300, 64, 8), (129, 320, 130, 32, 4),
                                              (64, 2048, 256, 128, 16), (1, 512, 128, 64, 8), (257, 64, 5, 64, 16),
                                              (5, 384, 130, 64, 8), (32, 2048, 70, 64, 16), (8, 320, 96, 32, 8),
-                                             (33, 1152, 200, 128, 32), (3, 128, 64, 64, 8)])
+                                             (33, 1152, 200, 128, 32), (3, 128, 64, 64, 8),
+                                             (4, 256, 64, 64, 8), (7, 768, 100, 64, 8), (12, 1024, 64, 64, 8),
+                                             (2, 1280, 70, 64, 8), (9, 2304, 64, 64, 8), (17, 2560, 40, 64, 8),
+                                             (3, 2816, 64, 64, 8), (20, 3072, 130, 64, 8), (6, 3328, 64, 64, 8)])
 def test_gemm_dynamic_accumulators_and_outputs(M, K, N, bank, topk):
     _say(f"gemm dynamic M={M} K={K} N={N} bank={bank} topk={topk}")
     bits, wq, sw = random_case(1000 + M + K + N, M, K, N, outliers=min(6, K // 16))
