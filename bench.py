@@ -54,6 +54,8 @@ def parse():
     ap.add_argument("--topk", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also replay the steps from a captured HIP graph (launch overhead removed; matters for few-token shapes)")
     ap.add_argument("--no-probes", action="store_true", help="skip the measured matrix-instruction and streaming rates")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the CPU-oracle sample (0: sized for about 20 s)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -320,6 +322,34 @@ def main():
     }
     if calibration is not None:
         out["calibration"] = calibration
+
+    if args.graph:
+        # The same steps replayed from a captured graph: the library only enqueues kernels, so a step can be
+        # captured; one graph holds enough steps to walk through every rotating buffer.
+        per_graph = int(np.lcm.reduce([n_x, n_y, 2, len(ws)]))
+        while per_graph < 8:
+            per_graph *= 2
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for i in range(per_graph):
+                    a = acts[i % 2]
+                    sq.sq_encode(p, xs[i % n_x], a, static_mask=md, stream=side)
+                    sq.sq_gemm(p, a, ws[i % len(ws)], ys[i % n_y], None, stream=side)
+        torch.cuda.synchronize()
+        replays = max(3, -(-args.steps // per_graph))
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - t0) * 1e3 / (replays * per_graph)
+        out["graph"] = {"ms_per_step": g_ms, "steps_per_graph": per_graph, "replays": replays,
+                        "effective_tops_2MNK": ops_eff / (g_ms * 1e-3) / 1e12,
+                        "weight_stream_gbs": gemm_bytes / (g_ms * 1e-3) / 1e9 if hbm_bound else None}
 
     if not args.no_probes:
         out["achievable"] = probes(torch, sq, xs, enc_bytes + enc_bytes_written_extra - M * K * 2)
