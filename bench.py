@@ -6,7 +6,8 @@ both integer products -> dequantised bf16 output.  The step is issued as sq_enco
 sq_gemm (exactly what sq_linear enqueues) so that HIP events between the two launches give the
 duration of each kernel inside the timed region.  Inputs are synthetic, seeded, already in HBM.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: throughput of the step, the roofline of the dominant kernel, the encoder's rate, measured
+chip rates, a dense W4A8 run of the same shape and the CPU oracle timed on a row sample.
 """
 from __future__ import annotations
 

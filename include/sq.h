@@ -26,6 +26,9 @@
  *     magnitude is subnormal gives unspecified codes.
  *   - No global state, no environment variables; calls on different streams are independent
  *     as long as their buffers (workspace included) are distinct.
+ *   - The calls may be captured into a HIP graph.  The first sq_gemm / sq_linear of a shape class on a
+ *     device raises that kernel's dynamic-LDS limit (hipFuncSetAttribute): make one call of the same shape
+ *     before starting a capture.
  */
 #ifndef SQ_H_
 #define SQ_H_
@@ -54,9 +57,11 @@ enum { SQ_OUT_F32 = 0, SQ_OUT_BF16 = 1 };
 /* Problem description.  Section 4.1 writes a setting as B-(h_high/h_low)-s: here B = bank,
  * h_high/h_low = 8/4, s = 1 - topk/bank. */
 typedef struct {
-  int32_t M, K, N;   /* tokens, input channels, output channels.  K % bank == 0, K % 64 == 0, K <= 131072 */
+  int32_t M, K, N;   /* tokens, input channels, output channels.  K % bank == 0, K % 64 == 0, K <= 131072,
+                        K / bank <= 512 */
   int32_t bank;      /* 32, 64 or 128 */
-  int32_t topk;      /* high-precision channels per bank, 1 <= topk <= bank/2 and topk <= 32 */
+  int32_t topk;      /* high-precision channels per bank: a power of two, <= 32 and <= bank/2; dynamic mode also
+                        >= bank/16 (the sparsities 1/2 ... 15/16 of Section 4.1); static mode: (K/bank)*topk % 32 == 0 */
   int32_t mode;      /* SQ_DYNAMIC or SQ_STATIC */
   int32_t out_dtype; /* SQ_OUT_F32 or SQ_OUT_BF16 */
 } sq_params;
