@@ -663,25 +663,36 @@ __device__ __forceinline__ void pipeline_barrier_after(const SkinnyOps<TI>& cur,
 // are a wave-uniform base (scalar registers, advanced by scalar additions) plus a per-lane 32-bit offset
 // that never changes.  (The instruction's immediate offset is no use here: for a copy into LDS it is added
 // to the LDS address as well.)
-template <int TI, int U>
+// LAST: the trip is the last one of the K loop (it ends at the last step): only its first steps still have a
+// copy to enqueue, its last step has no successor to fetch, and the barrier's allowance shrinks with the
+// copies that remain outstanding.
+template <int TI, int U, bool LAST = false>
 __device__ __forceinline__ void skinny_steady_step(const SkinnyOps<TI>& cur, SkinnyOps<TI>& nxt, const char* ub_lo,
                                                    const char* ub_hi, const unsigned (&l_lo)[SkinnyCfg<TI>::N_LO],
                                                    const unsigned (&l_hi)[SkinnyCfg<TI>::N_HI], char* lds, int wave,
                                                    int r, int h, v16i (&acc_lo)[TI], v16i (&acc_hi)[TI]) {
   typedef SkinnyCfg<TI> C;
   static_assert(8 % C::A_STAGES == 0 && 8 % C::W_STAGES == 0, "ring sizes must divide the trip length");
-  skinny_fetch_at<TI>(nxt, lds, (U + 1) % C::A_STAGES, (U + 1) % C::W_STAGES, wave, r, h);
-  char* dst = lds + ((U + C::A_DIST) % C::A_STAGES) * C::A_STAGE;
-  const char* s_lo = ub_lo + (U + C::A_DIST) * 64;
-  const char* s_hi = ub_hi + (U + C::A_DIST) * 128;
+  constexpr bool FETCH = !LAST || U + 1 < 8;
+  constexpr bool COPY = !LAST || U + C::A_DIST < 8;
+  // copies still outstanding at the barrier may be those of steps kt+U+3 ... : A_DIST-2 steps' worth in the
+  // steady state, in the last trip only up to its last step (step kt+7)
+  constexpr int YOUNGER = LAST ? (7 - (U + 2) > 0 ? 7 - (U + 2) : 0) : C::A_DIST - 2;
+  constexpr int PENDING = (YOUNGER < C::A_DIST - 2 ? YOUNGER : C::A_DIST - 2) * C::NA;
+  if (FETCH) skinny_fetch_at<TI>(nxt, lds, (U + 1) % C::A_STAGES, (U + 1) % C::W_STAGES, wave, r, h);
+  if (COPY) {
+    char* dst = lds + ((U + C::A_DIST) % C::A_STAGES) * C::A_STAGE;
+    const char* s_lo = ub_lo + (U + C::A_DIST) * 64;
+    const char* s_hi = ub_hi + (U + C::A_DIST) * 128;
 #pragma unroll
-  for (int i = 0; i < C::N_LO; ++i)
-    __builtin_amdgcn_global_load_lds(s_lo + l_lo[i], (lds_ptr_t)(dst + C::A_LO + (128 * i + 64 * wave) * 16), 16, 0, 0);
+    for (int i = 0; i < C::N_LO; ++i)
+      __builtin_amdgcn_global_load_lds(s_lo + l_lo[i], (lds_ptr_t)(dst + C::A_LO + (128 * i + 64 * wave) * 16), 16, 0, 0);
 #pragma unroll
-  for (int i = 0; i < C::N_HI; ++i)
-    __builtin_amdgcn_global_load_lds(s_hi + l_hi[i], (lds_ptr_t)(dst + C::A_HI + (128 * i + 64 * wave) * 16), 16, 0, 0);
+    for (int i = 0; i < C::N_HI; ++i)
+      __builtin_amdgcn_global_load_lds(s_hi + l_hi[i], (lds_ptr_t)(dst + C::A_HI + (128 * i + 64 * wave) * 16), 16, 0, 0);
+  }
   skinny_mma<TI>(cur, acc_lo, acc_hi);
-  pipeline_barrier<(C::A_DIST - 2) * C::NA>();  // the copies of steps <= kt + U + 2 have landed
+  pipeline_barrier<PENDING>();  // the copies of steps <= kt + U + 2 have landed
 }
 
 template <int TI>
@@ -797,6 +808,17 @@ __global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
       skinny_steady_step<TI, 7>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
       ub_lo += 8 * 64;
       ub_hi += 8 * 128;
+    }
+    if (steps - kt == 8) {  // exactly one trip left (K a multiple of 1024): the same code, winding down
+      skinny_steady_step<TI, 0, true>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, 1, true>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, 2, true>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, 3, true>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, 4, true>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, 5, true>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, 6, true>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, 7, true>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      kt += 8;
     }
   }
   // the remaining steps (fewer than 8 + A_DIST): stage indices and addresses computed at run time
