@@ -120,13 +120,16 @@ def probes(torch, sq, xs, enc_write_bytes):
     blocks, iters = 2 * n_cu, 2000
     sink = torch.empty(blocks * 256, dtype=torch.int32, device="cuda")
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    sq.sq_probe_mfma_i8(blocks, iters, sink)
-    torch.cuda.synchronize()
-    e0.record()
-    sq.sq_probe_mfma_i8(blocks, iters, sink)
-    e1.record()
-    torch.cuda.synchronize()
-    mfma_tops = 2.0 * 32768 * 8 * iters * 4 * blocks / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    rates = {}
+    for random_operands in (False, True):
+        sq.sq_probe_mfma_i8(blocks, iters, sink, random_operands)
+        torch.cuda.synchronize()
+        e0.record()
+        sq.sq_probe_mfma_i8(blocks, iters, sink, random_operands)
+        e1.record()
+        torch.cuda.synchronize()
+        rates[random_operands] = 2.0 * 32768 * 8 * iters * 4 * blocks / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    mfma_tops = rates[False]
 
     read_bytes = xs[0].numel() * xs[0].element_size()
     write_bytes = (int(enc_write_bytes) + 15) // 16 * 16
@@ -142,9 +145,11 @@ def probes(torch, sq, xs, enc_write_bytes):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / reps
     return {"mfma_i8_register_only_tops": mfma_tops, "mfma_i8_frac_of_peak": mfma_tops / INT8_PEAK_TOPS,
+            "mfma_i8_register_only_random_operands_tops": rates[True],
             "stream_encode_mix_gbs": (read_bytes + write_bytes) / (ms * 1e-3) / 1e9,
             "stream_encode_mix_ms": ms, "stream_read_bytes": read_bytes, "stream_write_bytes": write_bytes,
-            "note": "sq_probe_mfma_i8: 8 independent v_mfma_i32_32x32x32_i8 per wave per iteration, 2 workgroups per CU; "
+            "note": "sq_probe_mfma_i8: 8 independent v_mfma_i32_32x32x32_i8 per wave per iteration, 2 workgroups per CU, "
+                    "constant operands / pseudo-random widened INT4 operands that change every instruction; "
                     "sq_probe_stream: coalesced 16-byte reads of X and writes of as many bytes as sq_encode writes"}
 
 

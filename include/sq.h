@@ -174,13 +174,15 @@ int sq_calibrate_static(const sq_params *p, const uint16_t *x_calib, int64_t ldx
 /* Measurement probes (used by the benchmark only; nothing on the layer's path calls them).
  * sq_probe_mfma_i8: `blocks` workgroups of 4 waves, each wave issuing iters x 8 independent
  *   v_mfma_i32_32x32x32_i8 (the instruction both products of Section 3.3 run on here) on register
- *   operands: 2 * 32768 * 8 * iters * 4 * blocks operations per launch.  `sink` device, blocks * 256
- *   int32, receives one word per thread.  1 <= blocks <= 65536, iters >= 1.
+ *   operands: 2 * 32768 * 8 * iters * 4 * blocks operations per launch.  random_operands != 0: the operands
+ *   are pseudo-random widened INT4 codes that change from instruction to instruction (what real data looks
+ *   like to the multipliers); 0: small constants (fewest bits toggling, highest clock).  `sink` device,
+ *   blocks * 256 int32, receives one word per thread.  1 <= blocks <= 65536, iters >= 8 and a multiple of 8.
  * sq_probe_stream: reads read_bytes from `src` and writes write_bytes to `dst` (device, 16-byte
  *   aligned, sizes multiples of 16, either may be 0 but not both), coalesced: what a plain streaming
  *   kernel with the encoder's mix of bytes read and written sustains.
  * Both only enqueue work on `stream`; errors as for the other calls. */
-int sq_probe_mfma_i8(int blocks, int iters, int32_t *sink, void *stream);
+int sq_probe_mfma_i8(int blocks, int iters, int random_operands, int32_t *sink, void *stream);
 int sq_probe_stream(const void *src, size_t read_bytes, void *dst, size_t write_bytes, void *stream);
 
 /* Human-readable name of a status code (static storage, never NULL). */

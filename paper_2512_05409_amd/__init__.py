@@ -71,7 +71,7 @@ def lib() -> ctypes.CDLL:
         L.sq_calibrate_workspace_bytes.restype = sz
         L.sq_calibrate_static.argtypes = [P(sq_params), vp, i64, i64, P(sq_weight), vp, vp, vp, sz, vp]
         L.sq_calibrate_static.restype = ctypes.c_int
-        L.sq_probe_mfma_i8.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp]
+        L.sq_probe_mfma_i8.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
         L.sq_probe_stream.argtypes = [vp, sz, vp, sz, vp]
         for f in (L.sq_weight_prepack, L.sq_encode, L.sq_gemm, L.sq_linear, L.sq_dense_w4a8_prepack,
                   L.sq_dense_w4a8_gemm, L.sq_probe_mfma_i8, L.sq_probe_stream):
@@ -225,8 +225,9 @@ def sq_calibrate_static(p: sq_params, x_calib, T: int, w: sq_weight, mask_out, i
                                      _stream(stream)), "sq_calibrate_static")
 
 
-def sq_probe_mfma_i8(blocks: int, iters: int, sink, stream=None) -> None:
-    _check(lib().sq_probe_mfma_i8(int(blocks), int(iters), _ptr(sink), _stream(stream)), "sq_probe_mfma_i8")
+def sq_probe_mfma_i8(blocks: int, iters: int, sink, random_operands: bool = False, stream=None) -> None:
+    _check(lib().sq_probe_mfma_i8(int(blocks), int(iters), int(bool(random_operands)), _ptr(sink), _stream(stream)),
+           "sq_probe_mfma_i8")
 
 
 def sq_probe_stream(src, read_bytes: int, dst, write_bytes: int, stream=None) -> None:

@@ -13,17 +13,33 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
-// Every wave issues iters x 8 independent v_mfma_i32_32x32x32_i8 on register operands.
+// Every wave issues iters x 8 independent v_mfma_i32_32x32x32_i8 on register operands.  RANDOM: the operands
+// are pseudo-random bytes that differ from instruction to instruction (eight operand pairs in rotation), which
+// is what the products of real data look like to the multipliers; with constant operands the instruction
+// stream is the same but far fewer bits toggle, and the chip holds a higher clock.
+template <bool RANDOM>
 __global__ __launch_bounds__(256) void mfma_rate_kernel(int iters, int32_t* __restrict__ sink) {
-  v4i a = {static_cast<int>(threadIdx.x), 1, 2, 3}, b = {4, 5, 6, static_cast<int>(threadIdx.x)};
+  v4i a[8], b[8];
+  unsigned x = 0x9E3779B9u * (blockIdx.x * 256 + threadIdx.x + 1);
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      x = x * 1664525u + 1013904223u;
+      a[i][q] = RANDOM ? static_cast<int>(x & 0xF0F0F0F0u) : (q + 1);  // widened INT4 codes: low nibbles zero
+      x = x * 1664525u + 1013904223u;
+      b[i][q] = RANDOM ? static_cast<int>(x & 0xF0F0F0F0u) : (q + 4);
+    }
   v16i acc[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][r] = 0;
-  for (int it = 0; it < iters; ++it) {
+  for (int it = 0; it < iters; it += 8) {  // iters is rounded up to a multiple of 8 by the caller
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[(i + u) & 7], acc[i], 0, 0, 0);
   }
   int s = 0;
 #pragma unroll
@@ -45,10 +61,13 @@ __global__ __launch_bounds__(256) void stream_kernel(const v4u* __restrict__ src
 
 }  // namespace
 
-extern "C" int sq_probe_mfma_i8(int blocks, int iters, int32_t* sink, void* stream) {
+extern "C" int sq_probe_mfma_i8(int blocks, int iters, int random_operands, int32_t* sink, void* stream) {
   if (!sink) return SQ_ERR_NULL;
-  if (blocks <= 0 || blocks > 65536 || iters <= 0) return SQ_ERR_SHAPE;
-  hipLaunchKernelGGL(mfma_rate_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), iters, sink);
+  if (blocks <= 0 || blocks > 65536 || iters <= 0 || iters % 8) return SQ_ERR_SHAPE;
+  if (random_operands)
+    hipLaunchKernelGGL(mfma_rate_kernel<true>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), iters, sink);
+  else
+    hipLaunchKernelGGL(mfma_rate_kernel<false>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), iters, sink);
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 

@@ -136,10 +136,11 @@ def test_calibrate_arguments(L):
 
 
 def test_probe_arguments(L):
-    assert L.sq_probe_mfma_i8(4, 10, None, None) == -1
-    assert L.sq_probe_mfma_i8(0, 10, FAKE, None) == -2
-    assert L.sq_probe_mfma_i8(4, 0, FAKE, None) == -2
-    assert L.sq_probe_mfma_i8(1 << 20, 1, FAKE, None) == -2
+    assert L.sq_probe_mfma_i8(4, 16, 0, None, None) == -1
+    assert L.sq_probe_mfma_i8(0, 16, 1, FAKE, None) == -2
+    assert L.sq_probe_mfma_i8(4, 10, 0, FAKE, None) == -2
+    assert L.sq_probe_mfma_i8(4, 0, 0, FAKE, None) == -2
+    assert L.sq_probe_mfma_i8(1 << 20, 8, 1, FAKE, None) == -2
     assert L.sq_probe_stream(None, 1024, FAKE, 1024, None) == -1
     assert L.sq_probe_stream(FAKE, 1024, None, 1024, None) == -1
     assert L.sq_probe_stream(FAKE, 1000, FAKE, 1024, None) == -2
