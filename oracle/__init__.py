@@ -31,11 +31,26 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_from_source(source_text: str, out_path: str) -> str:
+    """Compile a given oracle source text with the oracle's own compiler flags (used by the test that plants
+    mistakes in the oracle and checks that the pins notice)."""
+    src = out_path + ".c"
+    with open(src, "w") as f:
+        f.write(source_text)
+    cmd = ["gcc", "-std=c99", "-O2", "-fopenmp", "-ffp-contract=off", "-fno-fast-math", "-fPIC",
+           "-shared", "-o", out_path, src, "-lm"]
+    subprocess.run(cmd, check=True)
+    return out_path
+
+
 def _load():
     global _lib
     if _lib is None:
-        build()
-        L = ctypes.CDLL(_LIB)
+        # SQ_ORACLE_LIB: a substitute library (only the mutation test sets it, for its child processes)
+        override = os.environ.get("SQ_ORACLE_LIB")
+        if not override:
+            build()
+        L = ctypes.CDLL(override or _LIB)
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
         L.sqo_num_threads.restype = i32
         L.sqo_select_dynamic.argtypes = [vp, i32, i32, i32, vp]
