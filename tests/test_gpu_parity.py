@@ -62,6 +62,17 @@ def test_encode_dynamic_bit_exact(bank, topk):
     assert_encoding_equal(act, oracle.encode(bits, bank, topk))
 
 
+@pytest.mark.parametrize("bank,topk", [(64, 8), (32, 2), (32, 4), (32, 8), (32, 16), (64, 4), (64, 16), (64, 32),
+                                       (128, 8), (128, 16), (128, 32)])
+@pytest.mark.parametrize("M,K", [(7, 1024), (32, 4096), (1, 8192)])
+def test_encode_dynamic_few_rows(M, K, bank, topk):
+    """A handful of rows (decode shapes), every format."""
+    _say(f"encode dynamic few rows M={M} K={K} bank={bank} topk={topk}")
+    bits, _, _ = random_case(3 * bank + topk + M + K, M=M, K=K, N=8)
+    p, act = run_encode(bits, bank, topk)
+    assert_encoding_equal(act, oracle.encode(bits, bank, topk))
+
+
 @pytest.mark.parametrize("M,K,bank,topk", [(1, 64, 64, 8), (3, 128, 128, 8), (5, 8192, 64, 8), (2, 11008, 64, 8),
                                            (2, 11008, 32, 4), (3, 16384, 32, 8), (130, 512, 64, 8), (9, 4096, 128, 16)])
 def test_encode_dynamic_shapes(M, K, bank, topk):
