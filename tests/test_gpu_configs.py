@@ -105,3 +105,30 @@ def test_config4_down7b_static():
 def test_config5_up70b(M):
     _say(f"config 5 M={M}")
     run_config(workloads.make("c5_up70b", M=M), n_rows=6)
+
+
+@pytest.mark.parametrize("name,M", [("c3_mlp7b", None), ("c5_up70b", 8), ("c5_up70b", 64), ("c4_down7b_static", None)])
+def test_full_size_runs_are_reproducible(name, M):
+    """The kernels use no atomics on the output path: repeated launches at full size, with every compute unit
+    busy, must give the same bytes (a hazard between pipeline stages would show up as a difference)."""
+    _say(f"reproducibility {name} M={M}")
+    wl = workloads.make(name) if M is None else workloads.make(name, M=M)
+    static = wl.mode == "static"
+    p = sq.params(wl.M, wl.K, wl.N, wl.bank, wl.topk, mode=sq.SQ_STATIC if static else sq.SQ_DYNAMIC,
+                  out_dtype=sq.SQ_OUT_BF16)
+    xd, wqd, swd = dev(wl.x_bits), dev(wl.wq_packed), dev(wl.w_scale)
+    md, pre = None, None
+    if static:
+        mask, _ = oracle.static_mask(wl.calib_bits, wl.wq_packed, wl.w_scale, wl.bank, wl.topk)
+        md = dev(mask)
+        pre = torch.empty(sq.sq_weight_prepack_bytes(p), dtype=torch.uint8, device="cuda")
+        sq.sq_weight_prepack(p, wqd, mask, md, pre)
+    w = sq.weight(wqd, swd, pre)
+    ws = torch.empty(sq.sq_linear_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    ys = [torch.empty(wl.M * wl.N, dtype=torch.int16, device="cuda") for _ in range(2)]
+    sq.sq_linear(p, xd, w, ys[0], ws, static_mask=md)
+    for rep in range(4):
+        sq.sq_linear(p, xd, w, ys[1], ws, static_mask=md)
+        torch.cuda.synchronize()
+        assert torch.equal(ys[0], ys[1]), f"launch {rep + 2} differs from the first"
+        ys[1].zero_()
