@@ -24,6 +24,7 @@
  * rows with power-of-two scales and exact half-way cases, the 2:4 special case
  * (Section 3.1), numpy int64 matmul of the unpacked operands, one-hot weights,
  * k = b (plain W4A8) and emptied-hi (plain W4A4) reductions, fp64 epilogue,
+ * hand-computed bf16 half-way patterns for the output rounding,
  * a hand-computed static-importance bank, and the equivalent-bit values printed in
  * the paper's Table 3.
  * Parity unpinned: nothing in the paper prints a worked encoding or product, so

@@ -149,3 +149,37 @@ def test_static_mask_finds_outlier_channels():
     H = dense_hi(enc).astype(np.int64)
     Wi = unpack_int4(wl.wq_packed).astype(np.int64)
     assert np.array_equal(out.acc_lo, D @ Wi.T) and np.array_equal(out.acc_hi, H @ Wi.T)
+
+
+def test_bf16_output_rounding_hand_computed_patterns():
+    """The bf16 output is round-half-to-even of the fp32 output.  Each row's output is made to be a chosen
+    fp32 bit pattern (accumulator 1 x per-token scale = that value, weight scale 1); the expected bf16
+    patterns below are worked out by hand from the definition: keep the upper 16 bits, look at the lower 16;
+    above 0x8000 round up, below round down, exactly 0x8000 round to the even upper half."""
+    cases = [
+        (0x3F808000, 0x3F80),  # 1 + 2^-8: half-way, 0x3F80 is even -> stays
+        (0x3F818000, 0x3F82),  # 1 + 3*2^-8: half-way, 0x3F81 is odd -> up
+        (0x3F808001, 0x3F81),  # just above half-way -> up
+        (0x3F807FFF, 0x3F80),  # just below half-way -> down
+        (0xBF808000, 0xBF80),  # the same magnitudes, negative (sign-magnitude: rounding is symmetric)
+        (0xBF818000, 0xBF82),
+        (0x3FFF8000, 0x4000),  # half-way with an odd, all-ones mantissa: the carry runs into the exponent -> 2.0
+        (0x3FFFFFFF, 0x4000),  # just under 2.0 -> 2.0
+        (0x3F800000, 0x3F80),  # exactly representable values are untouched
+        (0x40490FDB, 0x4049),  # pi -> 3.140625
+        (0x00000000, 0x0000),
+    ]
+    M, K = len(cases), 32
+    d = np.zeros((M, K), np.int8)
+    d[:, 1] = 1  # one low code of 1 in channel 1 (channel 0 is the bank's high channel, code 0)
+    mask = np.zeros((M, 1), np.uint32)
+    mask[:, 0] = 1
+    s_lo = np.array([c[0] for c in cases], np.uint32).view(np.float32)
+    enc = oracle.Encoded(M, K, 32, 1, 0, pack_int4(d), np.zeros((M, 1, 1), np.int8), mask, s_lo.copy(),
+                         np.ones(M, np.float32))
+    w = np.zeros((1, K), np.int8)
+    w[0, 1] = 1
+    out = oracle.gemm(enc, pack_int4(w), np.ones(1, np.float32))
+    assert np.array_equal(out.acc_lo[:, 0], np.ones(M, np.int32)) and not out.acc_hi.any()
+    assert [int(v) for v in out.y32.view(np.uint32)[:, 0]] == [c[0] for c in cases]
+    assert [hex(int(v)) for v in out.ybf16[:, 0]] == [hex(c[1]) for c in cases]

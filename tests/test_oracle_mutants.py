@@ -55,6 +55,10 @@ MUTANTS = [
      "a += fabs((double)bf16_value(calib[t * K + j]));", "a += (double)bf16_value(calib[t * K + j]);"),
     ("importance ignores the weights",
      "imp[j] = fabs(a * cs);", "imp[j] = fabs(a);"),
+    ("bf16 output rounds half-way cases up instead of to even",
+     "u += 0x7FFFu + ((u >> 16) & 1u);", "u += 0x8000u;"),
+    ("bf16 output truncates",
+     "u += 0x7FFFu + ((u >> 16) & 1u);", "u += 0u;"),
 ]
 
 
