@@ -21,14 +21,16 @@
  *     enqueues kernels on `stream` (a hipStream_t passed as void*; NULL = default stream)
  *     and returns.  Structs are read on the host during the call only.
  *   - Return value: SQ_OK (0) or a negative sq_status.  Invalid arguments never launch anything.
- *   - Data pointers must be 16-byte aligned and leading dimensions must keep rows 16-byte aligned.
+ *   - Data pointers must be 16-byte aligned (the workspace of sq_linear: 256-byte).  ldx must keep the rows of X
+ *     16-byte aligned; any ldy >= N is accepted (rows of Y that are 16-byte aligned are stored with vector stores).
  *   - Activations must be finite; NaN/Inf give unspecified codes.  A row part whose largest
  *     magnitude is subnormal gives unspecified codes.
- *   - No global state, no environment variables; calls on different streams are independent
- *     as long as their buffers (workspace included) are distinct.
- *   - The calls may be captured into a HIP graph.  The first sq_gemm / sq_linear of a shape class on a
- *     device raises that kernel's dynamic-LDS limit (hipFuncSetAttribute): make one call of the same shape
- *     before starting a capture.
+ *   - No environment variables.  The only process-wide state is one "initialised" flag per device: the first
+ *     launching call on a device (or sq_init) raises the dynamic-LDS limit of every kernel there
+ *     (hipFuncSetAttribute), under a mutex; afterwards the launch path reads that flag and nothing else.
+ *     Calls on different streams are independent as long as their buffers (workspace included) are distinct.
+ *   - The calls may be captured into a HIP graph once the device is initialised: call sq_init() (or any
+ *     launching entry point) on the device before starting a capture.
  */
 #ifndef SQ_H_
 #define SQ_H_
@@ -45,7 +47,7 @@ typedef enum {
   SQ_ERR_NULL = -1,        /* a required pointer is NULL */
   SQ_ERR_SHAPE = -2,       /* M, K, N <= 0; K % bank; K % 64; leading dimension too small; K too large */
   SQ_ERR_UNSUPPORTED = -3, /* bank / topk / mode / out_dtype outside the supported set; static mode without a mask */
-  SQ_ERR_ALIGN = -4,       /* pointer or leading dimension breaks the 16-byte alignment rule */
+  SQ_ERR_ALIGN = -4,       /* pointer or leading dimension breaks the alignment rule */
   SQ_ERR_LAUNCH = -5,      /* the HIP runtime refused a launch */
   SQ_ERR_MASK = -6,        /* (prepack, host check) a bank of the static mask does not hold exactly topk bits */
   SQ_ERR_WORKSPACE = -7    /* workspace NULL or smaller than sq_workspace_bytes() */
@@ -89,6 +91,11 @@ typedef struct {
   const float *scale;     /* [N] */
   const void *prepacked;  /* static mode: output of sq_weight_prepack (required); dynamic mode: ignored, may be NULL */
 } sq_weight;
+
+/* Per-device initialisation for the current device (idempotent, thread-safe): raises the kernels' dynamic-LDS
+ * limits.  Every launching entry point does this on its first call on a device; call it explicitly before a
+ * stream capture.  SQ_OK or SQ_ERR_LAUNCH. */
+int sq_init(void);
 
 /* Byte sizes of the four arrays of an sq_act for these parameters (scales: M floats each).
  * Returns the total; any out pointer may be NULL.  Returns 0 if the parameters are invalid. */
@@ -139,7 +146,14 @@ int sq_encode(const sq_params *p, const uint16_t *x_bf16, int64_t ldx, const uin
 int sq_gemm(const sq_params *p, const sq_act *a, const sq_weight *w, void *y, int64_t ldy,
             int32_t *acc_lo_dbg, int32_t *acc_hi_dbg, void *workspace, size_t workspace_bytes, void *stream);
 
-/* sq_encode into the workspace followed by sq_gemm: Y = SQ(X) . W^T, everything on `stream`. */
+/* Which of its kernels sq_gemm / sq_linear run for these parameters (static storage, never NULL):
+ * "tile128x256" (workgroup tile of 128 tokens x 256 output channels; shapes with more than 128 such tiles),
+ * "tile128x128" (fewer tiles), "tile64x64" (M <= 64), "stream32" (dynamic mode, M <= 32, K % 128 == 0: the
+ * weight-streaming decode kernel), or "invalid".  Informational: tests use it to state which kernel a case covers. */
+const char *sq_gemm_variant(const sq_params *p);
+
+/* sq_encode into the workspace followed by sq_gemm: Y = SQ(X) . W^T, everything on `stream`.
+ * workspace: device, 256-byte aligned, sq_linear_workspace_bytes(p) bytes, contents destroyed. */
 int sq_linear(const sq_params *p, const uint16_t *x_bf16, int64_t ldx, const uint32_t *static_mask,
               const sq_weight *w, void *y, int64_t ldy, void *workspace, size_t workspace_bytes, void *stream);
 

@@ -22,6 +22,7 @@ EXPORTS = (
     "sq_act_bytes", "sq_gemm_workspace_bytes", "sq_linear_workspace_bytes", "sq_weight_prepack_bytes",
     "sq_weight_prepack", "sq_encode", "sq_gemm", "sq_linear", "sq_dense_w4a8_prepack", "sq_dense_w4a8_gemm",
     "sq_calibrate_workspace_bytes", "sq_calibrate_static", "sq_probe_mfma_i8", "sq_probe_stream", "sq_status_string", "sq_version",
+    "sq_init", "sq_gemm_variant",
 )
 
 
@@ -79,6 +80,10 @@ def lib() -> ctypes.CDLL:
         L.sq_status_string.argtypes = [ctypes.c_int]
         L.sq_status_string.restype = ctypes.c_char_p
         L.sq_version.restype = ctypes.c_char_p
+        L.sq_init.argtypes = []
+        L.sq_init.restype = ctypes.c_int
+        L.sq_gemm_variant.argtypes = [P(sq_params)]
+        L.sq_gemm_variant.restype = ctypes.c_char_p
         _lib = L
     return _lib
 
@@ -89,6 +94,14 @@ def status_string(status: int) -> str:
 
 def version() -> str:
     return lib().sq_version().decode()
+
+
+def sq_init() -> None:
+    _check(lib().sq_init(), "sq_init")
+
+
+def sq_gemm_variant(p: "sq_params") -> str:
+    return lib().sq_gemm_variant(ctypes.byref(p)).decode()
 
 
 def params(M: int, K: int, N: int, bank: int = 64, topk: int = 8, mode: int = SQ_DYNAMIC,

@@ -2,7 +2,30 @@
 // synchronisation; every entry point only enqueues work on the caller's stream.
 #include <string.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "sq_device.h"
+
+namespace sq {
+
+// The only process-wide state of the library: one flag per device saying that the kernels' dynamic-LDS
+// limits have been raised there.
+int ensure_device_ready() {
+  static std::atomic<int> ready[64];
+  static std::mutex mu;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return SQ_ERR_LAUNCH;
+  if (ready[dev].load(std::memory_order_acquire)) return SQ_OK;
+  std::lock_guard<std::mutex> lock(mu);
+  if (ready[dev].load(std::memory_order_relaxed)) return SQ_OK;
+  int rc = init_gemm_kernels();
+  if (rc == SQ_OK) rc = init_encode_kernels();
+  if (rc == SQ_OK) ready[dev].store(1, std::memory_order_release);
+  return rc;
+}
+
+}  // namespace sq
 
 namespace {
 
@@ -67,6 +90,13 @@ int check_y(const sq_params* p, const void* y, int64_t ldy) {
 
 extern "C" {
 
+int sq_init(void) { return sq::ensure_device_ready(); }
+
+const char* sq_gemm_variant(const sq_params* p) {
+  if (check_params(p) != SQ_OK) return "invalid";
+  return sq::gemm_variant_name(p->M, p->N, p->K, p->mode == SQ_DYNAMIC);
+}
+
 size_t sq_act_bytes(const sq_params* p, size_t* d_lo, size_t* hi_val, size_t* mask, size_t* scale) {
   if (check_params(p) != SQ_OK) return 0;
   const ActLayout l = act_layout(p);
@@ -111,6 +141,7 @@ int sq_weight_prepack(const sq_params* p, const uint8_t* wq, const uint32_t* sta
     }
     if (c != p->topk) return SQ_ERR_MASK;
   }
+  if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
   return sq::launch_weight_prepack(p->N, p->K, p->bank, p->topk, k_hi_of(p), wq, static_mask,
                                    static_cast<uint8_t*>(out), static_cast<hipStream_t>(stream));
 }
@@ -136,6 +167,7 @@ int sq_calibrate_static(const sq_params* p, const uint16_t* x_calib, int64_t ldx
   const size_t need = sq_calibrate_workspace_bytes(p, T);
   if (!workspace || workspace_bytes < need) return SQ_ERR_WORKSPACE;
   if (!aligned16(workspace)) return SQ_ERR_ALIGN;
+  if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
   int ca, ra, cw, rw;
   sq::calibrate_chunks(T, p->N, &ca, &ra, &cw, &rw);
   double* pa = static_cast<double*>(workspace);
@@ -156,10 +188,12 @@ int sq_encode(const sq_params* p, const uint16_t* x_bf16, int64_t ldx, const uin
     if (!static_mask) return SQ_ERR_UNSUPPORTED;
     if (!out || !out->d_lo || !out->hi_val || !out->scale_lo || !out->scale_hi) return SQ_ERR_NULL;
     if (!aligned16(out->d_lo) || !aligned16(out->hi_val) || !aligned16(static_mask)) return SQ_ERR_ALIGN;
+    if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
     return sq::launch_encode_static(*p, x_bf16, ldx, static_mask, *out, static_cast<hipStream_t>(stream));
   }
   rc = check_act(p, out);
   if (rc != SQ_OK) return rc;
+  if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
   return sq::launch_encode_dynamic(*p, x_bf16, ldx, *out, static_cast<hipStream_t>(stream));
 }
 
@@ -173,6 +207,7 @@ int sq_gemm(const sq_params* p, const sq_act* a, const sq_weight* w, void* y, in
   const bool need_ws = p->mode == SQ_DYNAMIC && !a->hi_dense;
   if (need_ws && (!workspace || workspace_bytes < sq_gemm_workspace_bytes(p))) return SQ_ERR_WORKSPACE;
   if (need_ws && !aligned16(workspace)) return SQ_ERR_ALIGN;
+  if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   sq::GemmArgs g;
@@ -259,6 +294,7 @@ int sq_dense_w4a8_gemm(const sq_params* p, const int8_t* a_i8, const float* a_sc
   int rc = check_y(p, y, ldy);
   if (rc != SQ_OK) return rc;
   if (!aligned16(a_i8) || !aligned16(w->prepacked)) return SQ_ERR_ALIGN;
+  if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
   sq::GemmArgs g;
   memset(&g, 0, sizeof g);
   g.M = p->M;

@@ -10,7 +10,13 @@ namespace sq {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-// ---- launchers (defined in the .hip files, called by the C ABI in sq_api.hip) ----
+// ---- per-device initialisation (sq_api.cpp): raises the dynamic-LDS limits of the kernels, once per
+// device; every launching entry point calls it. ----
+int ensure_device_ready();
+int init_gemm_kernels();     // sq_gemm.hip
+int init_encode_kernels();   // sq_encode.hip
+
+// ---- launchers (defined in the .hip files, called by the C ABI in sq_api.cpp) ----
 
 // X -> SQ-format, dynamic rule (per-token top-k by magnitude inside each bank).
 int launch_encode_dynamic(const sq_params& p, const uint16_t* x, int64_t ldx, const sq_act& out, hipStream_t st);
@@ -49,5 +55,7 @@ struct GemmArgs {
   int32_t* acc_hi_dbg;
 };
 int launch_gemm(const GemmArgs& g, hipStream_t st);
+// Name of the kernel variant launch_gemm picks for a shape ("tile128x256", "tile128x128", "tile64x64", "stream32").
+const char* gemm_variant_name(int M, int N, int K, bool dynamic);
 
 }  // namespace sq

@@ -459,12 +459,8 @@ __global__ __launch_bounds__(256) void weight_prepack_kernel(int N, int K, int B
 template <int B, int KT, int MAXT>
 int launch_dyn_t(const sq_params& p, const uint16_t* x, int64_t ldx, const sq_act& o, hipStream_t st, int G, int R,
                  int threads, int blocks) {
+  // up to MAXT * B bytes; the limit of every instantiation was raised by init_encode_kernels
   const size_t lds = o.hi_dense ? static_cast<size_t>(threads) * B : 0;
-  if (lds > 32768) {  // only very long rows with bank 128: ask for the larger dynamic LDS window
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(encode_dynamic_kernel<B, KT, MAXT>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
-      return SQ_ERR_LAUNCH;
-  }
   hipLaunchKernelGGL((encode_dynamic_kernel<B, KT, MAXT>), dim3(blocks), dim3(threads), lds, st, x, ldx, p.M, p.K, G, R,
                      o.d_lo, o.hi_val, o.mask, o.scale_lo, o.scale_hi, o.hi_dense);
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
@@ -501,7 +497,27 @@ int launch_stat(const sq_params& p, const uint16_t* x, int64_t ldx, const uint32
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
+template <int B, int KT, int MAXT>
+hipError_t raise_encode_lds_limit() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(encode_dynamic_kernel<B, KT, MAXT>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, MAXT * B);
+}
+
 }  // namespace
+
+// Long rows with bank 128 need more dynamic LDS for the hi_dense staging than the default limit: raised here
+// for every instantiation, once per device (library initialisation, never on the launch path).
+int init_encode_kernels() {
+  hipError_t e = hipSuccess;
+#define SQ_CASE(B, KT)                                                        \
+  if (e == hipSuccess) e = raise_encode_lds_limit<B, KT, 256>();              \
+  if (e == hipSuccess) e = raise_encode_lds_limit<B, KT, 512>();
+  SQ_CASE(32, 2) SQ_CASE(32, 4) SQ_CASE(32, 8) SQ_CASE(32, 16)
+  SQ_CASE(64, 4) SQ_CASE(64, 8) SQ_CASE(64, 16) SQ_CASE(64, 32)
+  SQ_CASE(128, 8) SQ_CASE(128, 16) SQ_CASE(128, 32)
+#undef SQ_CASE
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
 
 int launch_encode_dynamic(const sq_params& p, const uint16_t* x, int64_t ldx, const sq_act& out, hipStream_t st) {
   // K / bank <= 512 is checked by the caller.

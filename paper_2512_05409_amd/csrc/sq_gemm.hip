@@ -359,18 +359,16 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm,
 // latency hides under the K loop.
 template <typename T>
 struct EpiScales {
-  float slo, shi;    // thread t < BM: s_lo / 256 and s_hi / 16 of row m0 + t
+  float slo, shi;    // thread t < BM: s_lo and s_hi of row m0 + t
   float sw[T::TJ];   // s_w of this lane's column in each of the wave's 32-column tiles
 };
 
 template <typename T>
 __device__ __forceinline__ void load_epi_scales(EpiScales<T>& e, const GemmArgs& g, int m0, int n0, int wn, int lane) {
-  // The accumulators carry the widening factors (256 and 16); folding the inverse powers of two into the
-  // scales is exact and leaves every rounding of the epilogue where it was.
   const int tid = threadIdx.x;
   const int m = min(m0 + (tid < T::BM ? tid : 0), g.M - 1);
-  e.slo = g.s_lo ? g.s_lo[m] * (1.0f / 256.0f) : 0.0f;
-  e.shi = g.s_hi[m] * (1.0f / 16.0f);
+  e.slo = g.s_lo ? g.s_lo[m] : 0.0f;
+  e.shi = g.s_hi[m];
 #pragma unroll
   for (int j = 0; j < T::TJ; ++j) {
     const int n = n0 + wn * T::WN + j * 32 + (lane & 31);
@@ -411,8 +409,9 @@ __device__ __forceinline__ void epilogue_typed(const GemmArgs& g, const EpiScale
       for (int e = 0; e < 4; ++e) {
 #pragma unroll
         for (int j = 0; j < T::TJ; ++j) {
-          float t = __fmul_rn(static_cast<float>(acc_lo[i][j][4 * rq + e]), slo[e]);
-          t = __fmaf_rn(static_cast<float>(acc_hi[i][j][4 * rq + e]), shi[e], t);
+          // the accumulators carry the widening factors 256 and 16: shifted out exactly, as integers
+          float t = __fmul_rn(static_cast<float>(acc_lo[i][j][4 * rq + e] >> 8), slo[e]);
+          t = __fmaf_rn(static_cast<float>(acc_hi[i][j][4 * rq + e] >> 4), shi[e], t);
           const float y = __fmul_rn(t, es.sw[j]);
           OutT* dst = reinterpret_cast<OutT*>(tb + (rl0 + e) * ROW) + j * 32 + (lane & 31);
           if constexpr (ESZ == 2) *dst = bf16_rne(y);
@@ -521,17 +520,6 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmArgs g) {
 
 template <typename T, int MODE>
 int launch_mode(const GemmArgs& g, hipStream_t st) {
-  // The kernel needs more dynamic LDS than the default limit; raising it is per device and
-  // idempotent, so a race between threads only repeats the call.
-  static bool attr_done[64] = {};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return SQ_ERR_LAUNCH;
-  if (!attr_done[dev]) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<T, MODE>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES) != hipSuccess)
-      return SQ_ERR_LAUNCH;
-    attr_done[dev] = true;
-  }
   const int tiles = ((g.N + T::BN - 1) / T::BN) * ((g.M + T::BM - 1) / T::BM);
   const int blocks = (tiles + 7) / 8 * 8;
   hipLaunchKernelGGL((gemm_kernel<T, MODE>), dim3(blocks), dim3(NT), T::LDS_BYTES, st, g);
@@ -749,15 +737,15 @@ __global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
     p_hi[i] = reinterpret_cast<const char*>(g.a_hi_dense) + static_cast<int64_t>(min(row, g.M - 1)) * g.K + c * 16;
   }
 
-  // per-token scales of the rows this lane's accumulator registers hold, with the widening factors folded in
+  // per-token scales of the rows this lane's accumulator registers hold
   float slo[TI][16], shi[TI][16];
 #pragma unroll
   for (int i = 0; i < TI; ++i)
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
       const int m = min(i * 32 + 8 * (q >> 2) + 4 * h + (q & 3), g.M - 1);
-      slo[i][q] = g.s_lo[m] * (1.0f / 256.0f);
-      shi[i][q] = g.s_hi[m] * (1.0f / 16.0f);
+      slo[i][q] = g.s_lo[m];
+      shi[i][q] = g.s_hi[m];
     }
   const int n = n0 + wave * 32 + r;
   const float sw = g.s_w[min(n, g.N - 1)];
@@ -849,8 +837,8 @@ __global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
       for (int q = 0; q < 16; ++q) {
         const int m = i * 32 + 8 * (q >> 2) + 4 * h + (q & 3);
         if (m < g.M) {
-          float t = __fmul_rn(static_cast<float>(acc_lo[i][q]), slo[i][q]);
-          t = __fmaf_rn(static_cast<float>(acc_hi[i][q]), shi[i][q], t);
+          float t = __fmul_rn(static_cast<float>(acc_lo[i][q] >> 8), slo[i][q]);
+          t = __fmaf_rn(static_cast<float>(acc_hi[i][q] >> 4), shi[i][q], t);
           const float y = __fmul_rn(t, sw);
           const int64_t o = static_cast<int64_t>(m) * g.ldy + n;
           if (g.out_bf16) reinterpret_cast<uint16_t*>(g.y)[o] = bf16_rne(y);
@@ -865,43 +853,74 @@ __global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
 template <int TI>
 int launch_skinny(const GemmArgs& g, hipStream_t st) {
   typedef SkinnyCfg<TI> C;
-  static bool attr_done[64] = {};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return SQ_ERR_LAUNCH;
-  if (!attr_done[dev]) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<TI>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) != hipSuccess)
-      return SQ_ERR_LAUNCH;
-    attr_done[dev] = true;
-  }
   hipLaunchKernelGGL((gemm_skinny_kernel<TI>), dim3((g.N + C::BN - 1) / C::BN), dim3(C::THREADS), C::LDS_BYTES, st, g);
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
+typedef Tile<128, 256> Big;   // matrix-core bound shapes
+typedef Tile<64, 64> Skinny;  // M <= 64 (decode): bound by streaming the INT4 weights once from HBM, so the
+                              // tile is narrow in N to spread the weight rows over every compute unit
+                              // (several small workgroups per unit keep enough loads in flight)
+typedef Tile<128, 128> Mid;   // shapes with too few 128x256 tiles to occupy every compute unit
+
+enum Variant { V_BIG, V_MID, V_SMALL, V_STREAM };
+
+// Which kernel a shape runs on.  dynamic: the call has the low operand and the zero-padded high image.
+Variant pick_variant(int M, int N, int K, bool dynamic) {
+  if (M <= 64) return (dynamic && M <= 32 && K % KS == 0) ? V_STREAM : V_SMALL;
+  const int64_t big_tiles = static_cast<int64_t>((M + 127) / 128) * ((N + 255) / 256);
+  return big_tiles <= 128 ? V_MID : V_BIG;  // then twice as many half-size tiles still run in one round
+}
+
+template <typename T, int MODE>
+hipError_t raise_lds_limit() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<T, MODE>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+}
+
+template <int MODE>
+int launch_for_mode(const GemmArgs& g, hipStream_t st, Variant v) {
+  if (v == V_BIG) return launch_mode<Big, MODE>(g, st);
+  if (v == V_MID) return launch_mode<Mid, MODE>(g, st);
+  return launch_mode<Skinny, MODE>(g, st);
+}
+
 }  // namespace
 
+// The GEMM kernels use more dynamic LDS than the default limit; the limit of every instantiation is raised
+// here, once per device (called by the library's per-device initialisation, never on the launch path).
+int init_gemm_kernels() {
+  hipError_t e = hipSuccess;
+#define SQ_RAISE(T)                                          \
+  if (e == hipSuccess) e = raise_lds_limit<T, 0>();          \
+  if (e == hipSuccess) e = raise_lds_limit<T, 1>();          \
+  if (e == hipSuccess) e = raise_lds_limit<T, 2>();
+  SQ_RAISE(Big) SQ_RAISE(Mid) SQ_RAISE(Skinny)
+#undef SQ_RAISE
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<1>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, SkinnyCfg<1>::LDS_BYTES);
+  return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+const char* gemm_variant_name(int M, int N, int K, bool dynamic) {
+  switch (pick_variant(M, N, K, dynamic)) {
+    case V_BIG: return "tile128x256";
+    case V_MID: return "tile128x128";
+    case V_SMALL: return "tile64x64";
+    default: return "stream32";
+  }
+}
+
 int launch_gemm(const GemmArgs& g, hipStream_t st) {
-  typedef Tile<128, 256> Big;   // matrix-core bound shapes
-  typedef Tile<64, 64> Skinny;  // M <= 64 (decode): bound by streaming the INT4 weights once from HBM, so the
-                                // tile is narrow in N to spread the weight rows over every compute unit
-                                // (several small workgroups per unit keep enough loads in flight)
-  typedef Tile<128, 128> Mid;   // shapes with too few 128x256 tiles to occupy every compute unit
-  const bool skinny = g.M <= 64;
-  const int64_t big_tiles = static_cast<int64_t>((g.M + 127) / 128) * ((g.N + 255) / 256);
-  const bool mid = !skinny && big_tiles <= 128;  // then twice as many half-size tiles still run in one round
-  if (g.a_lo && g.a_hi_dense) {
-    if (g.M <= 32 && g.K % KS == 0) return launch_skinny<1>(g, st);
-    if (skinny) return launch_mode<Skinny, 0>(g, st);
-    return mid ? launch_mode<Mid, 0>(g, st) : launch_mode<Big, 0>(g, st);
+  const bool dynamic = g.a_lo && g.a_hi_dense;
+  const Variant v = pick_variant(g.M, g.N, g.K, dynamic);
+  if (dynamic) {
+    if (v == V_STREAM) return launch_skinny<1>(g, st);
+    return launch_for_mode<0>(g, st, v);
   }
-  if (g.a_lo && g.a_hi_compact) {
-    if (skinny) return launch_mode<Skinny, 1>(g, st);
-    return mid ? launch_mode<Mid, 1>(g, st) : launch_mode<Big, 1>(g, st);
-  }
-  if (!g.a_lo && g.a_hi_compact) {
-    if (skinny) return launch_mode<Skinny, 2>(g, st);
-    return mid ? launch_mode<Mid, 2>(g, st) : launch_mode<Big, 2>(g, st);
-  }
+  if (g.a_lo && g.a_hi_compact) return launch_for_mode<1>(g, st, v);
+  if (!g.a_lo && g.a_hi_compact) return launch_for_mode<2>(g, st, v);
   return SQ_ERR_UNSUPPORTED;
 }
 

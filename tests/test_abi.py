@@ -164,3 +164,15 @@ def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(ValueError):
         sq._ptr(torch.zeros(4))
+
+
+def test_gemm_variant_names(L):
+    """Which kernel a shape runs on (the GPU tests use this to state what they cover)."""
+    assert sq.sq_gemm_variant(sq.params(4096, 4096, 22016)) == "tile128x256"      # 32 x 86 tiles
+    assert sq.sq_gemm_variant(sq.params(1500, 320, 6100)) == "tile128x256"        # 12 x 24 tiles
+    assert sq.sq_gemm_variant(sq.params(200, 1024, 300)) == "tile128x128"
+    assert sq.sq_gemm_variant(sq.params(64, 8192, 28672)) == "tile64x64"
+    assert sq.sq_gemm_variant(sq.params(8, 8192, 28672)) == "stream32"
+    assert sq.sq_gemm_variant(sq.params(8, 8192 + 64, 28672)) == "tile64x64"      # K % 128 != 0
+    assert sq.sq_gemm_variant(sq.params(8, 8192, 28672, mode=sq.SQ_STATIC)) == "tile64x64"
+    assert sq.sq_gemm_variant(sq.params(8, 100, 64)) == "invalid"

@@ -147,10 +147,10 @@ def run_gemm(p, enc_host, wq, sw, out_dtype, prepacked=None, static_mask=None):
     return yh, alo.host(np.int32).reshape(M, N), ahi.host(np.int32).reshape(M, N)
 
 
-# shapes chosen to reach every kernel variant: the 128x256 tile (M > 64), the 64x64 tile (32 < M <= 64, or
-# M <= 32 with K % 128 != 0), the weight-streaming kernel (M <= 32, K % 128 == 0) with 1 ... 26 K steps
-# (fewer than its rings hold, exactly as many, the first trip of the steady state, several tail lengths),
-# ragged M / N / K edges
+# shapes chosen to reach the small kernel variants: the 128x128 tile (M > 64 with few tiles), the 64x64 tile
+# (32 < M <= 64, or M <= 32 with K % 128 != 0), the weight-streaming kernel (M <= 32, K % 128 == 0) with
+# 1 ... 26 K steps (fewer than its rings hold, exactly as many, the first trip of the steady state, several
+# tail lengths), ragged M / N / K edges.  The 128x256 tile needs more than 128 tiles: test_gpu_big_tile.py.
 @pytest.mark.parametrize("M,K,N,bank,topk", [(16, 512, 512, 64, 8), (200, 1024, 300, 64, 8), (129, 320, 130, 32, 4),
                                              (64, 2048, 256, 128, 16), (1, 512, 128, 64, 8), (257, 64, 5, 64, 16),
                                              (5, 384, 130, 64, 8), (32, 2048, 70, 64, 16), (8, 320, 96, 32, 8),
