@@ -50,7 +50,8 @@ typedef enum {
   SQ_ERR_ALIGN = -4,       /* pointer or leading dimension breaks the alignment rule */
   SQ_ERR_LAUNCH = -5,      /* the HIP runtime refused a launch */
   SQ_ERR_MASK = -6,        /* (prepack, host check) a bank of the static mask does not hold exactly topk bits */
-  SQ_ERR_WORKSPACE = -7    /* workspace NULL or smaller than sq_workspace_bytes() */
+  SQ_ERR_WORKSPACE = -7,   /* workspace NULL or smaller than sq_workspace_bytes() */
+  SQ_ERR_SCRATCH = -8      /* sq_linear_noalloc: the problem needs more than SQ_NOALLOC_SCRATCH_BYTES of workspace */
 } sq_status;
 
 enum { SQ_DYNAMIC = 0, SQ_STATIC = 1 };
@@ -94,7 +95,7 @@ typedef struct {
 
 /* Per-device initialisation for the current device (idempotent, thread-safe): raises the kernels' dynamic-LDS
  * limits.  Every launching entry point does this on its first call on a device; call it explicitly before a
- * stream capture.  SQ_OK or SQ_ERR_LAUNCH. */
+ * stream capture.  Also looks up the address of sq_linear_noalloc's scratch array.  SQ_OK or SQ_ERR_LAUNCH. */
 int sq_init(void);
 
 /* Byte sizes of the four arrays of an sq_act for these parameters (scales: M floats each).
@@ -156,6 +157,23 @@ const char *sq_gemm_variant(const sq_params *p);
  * workspace: device, 256-byte aligned, sq_linear_workspace_bytes(p) bytes, contents destroyed. */
 int sq_linear(const sq_params *p, const uint16_t *x_bf16, int64_t ldx, const uint32_t *static_mask,
               const sq_weight *w, void *y, int64_t ldy, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * sq_linear for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments and result as sq_linear, without the workspace:
+ * the encoded activations between sq_encode and sq_gemm are kept in a fixed device array inside the
+ * library (SQ_NOALLOC_SCRATCH_BYTES per GPU the library runs on, held until the process ends).  The call
+ * allocates and frees nothing.  Limit: sq_linear_workspace_bytes(p) <= SQ_NOALLOC_SCRATCH_BYTES (decode and
+ * small prefill batches, e.g. 512 tokens x 8192 channels), otherwise SQ_ERR_SCRATCH and nothing is launched.
+ * All calls on one GPU share that GPU's array, whatever their stream: calls that overlap in time on one GPU
+ * race, so order them (one stream, or events).  The array keeps the previous call's contents; nothing in it
+ * has to start at zero, every byte that is read was written earlier in the same call.
+ * The array's address is looked up on the first launching call on a device or by sq_init: do one of them
+ * before a capture starts.
+ */
+#define SQ_NOALLOC_SCRATCH_BYTES (8u << 20)
+int sq_linear_noalloc(const sq_params *p, const uint16_t *x_bf16, int64_t ldx, const uint32_t *static_mask,
+                      const sq_weight *w, void *y, int64_t ldy, void *stream);
 
 /* Reference point for the benchmark: a plain per-token W4A8 layer (no SQ split) on the same
  * INT8 matrix-core kernel, which is what Section 4.2 says W4A8 falls back to on GPUs.

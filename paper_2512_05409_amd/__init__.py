@@ -22,8 +22,9 @@ EXPORTS = (
     "sq_act_bytes", "sq_gemm_workspace_bytes", "sq_linear_workspace_bytes", "sq_weight_prepack_bytes",
     "sq_weight_prepack", "sq_encode", "sq_gemm", "sq_linear", "sq_dense_w4a8_prepack", "sq_dense_w4a8_gemm",
     "sq_calibrate_workspace_bytes", "sq_calibrate_static", "sq_probe_mfma_i8", "sq_probe_stream", "sq_status_string", "sq_version",
-    "sq_init", "sq_gemm_variant",
+    "sq_init", "sq_gemm_variant", "sq_linear_noalloc",
 )
+SQ_NOALLOC_SCRATCH_BYTES = 8 << 20
 
 
 class SqError(RuntimeError):
@@ -66,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.sq_encode.argtypes = [P(sq_params), vp, i64, vp, P(sq_act), vp]
         L.sq_gemm.argtypes = [P(sq_params), P(sq_act), P(sq_weight), vp, i64, vp, vp, vp, sz, vp]
         L.sq_linear.argtypes = [P(sq_params), vp, i64, vp, P(sq_weight), vp, i64, vp, sz, vp]
+        L.sq_linear_noalloc.argtypes = [P(sq_params), vp, i64, vp, P(sq_weight), vp, i64, vp]
+        L.sq_linear_noalloc.restype = ctypes.c_int
         L.sq_dense_w4a8_prepack.argtypes = [P(sq_params), vp, vp, vp]
         L.sq_dense_w4a8_gemm.argtypes = [P(sq_params), vp, vp, P(sq_weight), vp, i64, vp]
         L.sq_calibrate_workspace_bytes.argtypes = [P(sq_params), i64]
@@ -220,6 +223,13 @@ def sq_linear(p: sq_params, x_bf16, w: sq_weight, y, workspace, static_mask=None
     _check(lib().sq_linear(ctypes.byref(p), _ptr(x_bf16), p.K if ldx is None else ldx, _ptr(static_mask),
                            ctypes.byref(w), _ptr(y), p.N if ldy is None else ldy, _ptr(workspace),
                            workspace.numel() * workspace.element_size(), _stream(stream)), "sq_linear")
+
+
+def sq_linear_noalloc(p: sq_params, x_bf16, w: sq_weight, y, static_mask=None, ldx: Optional[int] = None,
+                      ldy: Optional[int] = None, stream=None) -> None:
+    _check(lib().sq_linear_noalloc(ctypes.byref(p), _ptr(x_bf16), p.K if ldx is None else ldx, _ptr(static_mask),
+                                   ctypes.byref(w), _ptr(y), p.N if ldy is None else ldy, _stream(stream)),
+           "sq_linear_noalloc")
 
 
 def sq_dense_w4a8_prepack(p: sq_params, wq, out, stream=None) -> None:

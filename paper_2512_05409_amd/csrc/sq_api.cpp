@@ -10,7 +10,7 @@
 namespace sq {
 
 // The only process-wide state of the library: one flag per device saying that the kernels' dynamic-LDS
-// limits have been raised there.
+// limits have been raised and the scratch array of sq_linear_noalloc has been located there.
 int ensure_device_ready() {
   static std::atomic<int> ready[64];
   static std::mutex mu;
@@ -21,6 +21,7 @@ int ensure_device_ready() {
   if (ready[dev].load(std::memory_order_relaxed)) return SQ_OK;
   int rc = init_gemm_kernels();
   if (rc == SQ_OK) rc = init_encode_kernels();
+  if (rc == SQ_OK) rc = init_scratch(dev);
   if (rc == SQ_OK) ready[dev].store(1, std::memory_order_release);
   return rc;
 }
@@ -322,6 +323,7 @@ const char* sq_status_string(int status) {
     case SQ_ERR_LAUNCH: return "SQ_ERR_LAUNCH: the HIP runtime refused a launch";
     case SQ_ERR_MASK: return "SQ_ERR_MASK: a bank of the static mask does not hold exactly topk bits";
     case SQ_ERR_WORKSPACE: return "SQ_ERR_WORKSPACE: workspace missing or too small";
+    case SQ_ERR_SCRATCH: return "SQ_ERR_SCRATCH: the problem needs more than the built-in scratch of sq_linear_noalloc";
     default: return "unknown sq_status";
   }
 }

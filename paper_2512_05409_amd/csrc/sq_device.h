@@ -10,11 +10,12 @@ namespace sq {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-// ---- per-device initialisation (sq_api.cpp): raises the dynamic-LDS limits of the kernels, once per
-// device; every launching entry point calls it. ----
+// ---- per-device initialisation (sq_api.cpp): raises the dynamic-LDS limits of the kernels and looks up
+// the address of the no-allocation scratch array, once per device; every launching entry point calls it. ----
 int ensure_device_ready();
 int init_gemm_kernels();     // sq_gemm.hip
 int init_encode_kernels();   // sq_encode.hip
+int init_scratch(int dev);   // sq_noalloc.hip
 
 // ---- launchers (defined in the .hip files, called by the C ABI in sq_api.cpp) ----
 

@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported(L):
 
 def test_status_strings(L):
     assert sq.status_string(0) == "SQ_OK"
-    for code in range(-7, 0):
+    for code in range(-8, 0):
         assert sq.status_string(code).startswith("SQ_ERR_")
     assert "unknown" in sq.status_string(-99)
     assert sq.version()
