@@ -21,6 +21,12 @@ int init_scratch(int dev);   // sq_noalloc.hip
 
 // X -> SQ-format, dynamic rule (per-token top-k by magnitude inside each bank).
 int launch_encode_dynamic(const sq_params& p, const uint16_t* x, int64_t ldx, const sq_act& out, hipStream_t st);
+// The streaming kernel of the dynamic rule (sq_encode_dyn.hip): which shapes it takes, its one-time
+// initialisation, and its launcher.  image: hi_dense (two scales) or the combined INT8 operand (tied), or null.
+bool encode_stream_supports(const sq_params& p);
+int init_encode_stream_kernels();
+int launch_encode_stream(const sq_params& p, const uint16_t* x, int64_t ldx, const sq_act& out, int8_t* image, bool tied,
+                         float q_hi, float q_lo, hipStream_t st);
 // X -> SQ-format, static rule (channel mask shared by all tokens).
 int launch_encode_static(const sq_params& p, const uint16_t* x, int64_t ldx, const uint32_t* mask, const sq_act& out,
                          hipStream_t st);
