@@ -169,3 +169,36 @@ def stored_bits(h_high: float, h_low: float, s: float, explicit_mask: bool = Tru
     """Bits per element of the layout used here: the low part is kept dense (zeros at the
     high positions), the high part compact, plus one mask bit per element when the mask is explicit."""
     return h_low + (1.0 - s) * h_high + (1.0 if explicit_mask else 0.0)
+
+
+# ---- tied-scale variant (oracle/tied.py, plain numpy) ----
+_tied_mod = None
+
+
+def _tied():
+    """oracle.tied, or -- only for the test that plants mistakes in it -- the copy named by SQ_ORACLE_TIED_SRC."""
+    global _tied_mod
+    if _tied_mod is None:
+        import importlib
+        import importlib.util
+
+        override = os.environ.get("SQ_ORACLE_TIED_SRC")
+        if override:
+            spec = importlib.util.spec_from_file_location(__name__ + ".tied_variant", override)
+            mod = importlib.util.module_from_spec(spec)
+            mod.__package__ = __name__
+            spec.loader.exec_module(mod)
+            _tied_mod = mod
+        else:
+            _tied_mod = importlib.import_module(__name__ + ".tied")
+    return _tied_mod
+
+
+def encode_tied(x_bits: np.ndarray, bank: int, topk: int):
+    """X bf16 bits [M, K] -> SQ-format with tied scales (s_lo = 16 * s_hi); see oracle/tied.py."""
+    return _tied().encode_tied(x_bits, bank, topk)
+
+
+def gemm_tied(enc, wq_packed: np.ndarray, w_scale: np.ndarray):
+    """The single integer product of the tied-scale layer and its dequantised output."""
+    return _tied().gemm_tied(enc, wq_packed, w_scale)
