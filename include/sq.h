@@ -54,7 +54,15 @@ typedef enum {
   SQ_ERR_SCRATCH = -8      /* sq_linear_noalloc: the problem needs more than SQ_NOALLOC_SCRATCH_BYTES of workspace */
 } sq_status;
 
-enum { SQ_DYNAMIC = 0, SQ_STATIC = 1 };
+/* SQ_DYNAMIC_TIED: the dynamic rule with the two scales of a token tied, s_lo = 16 * s_hi (a variant for
+ * hardware whose low- and high-precision products cost the same, cf. Sections 3.3 and 5.2): an INT4 low code d
+ * stands for the INT8 value 16*d, the row is one INT8 operand, the layer one product with one accumulator:
+ *     A = max(amax_hi, amax_lo * 127/112)   s_hi = A / 127   s_lo = 16 * s_hi
+ *     acc[m,n] = sum_j c[m,j] * Wq[n,j],  c = high code at high channels, 16 * low code elsewhere
+ *     Y[m,n]   = (acc * s_hi[m]) * s_w[n]
+ * The stored format (d_lo, hi_val, mask, scales) is the same; sq_act::hi_dense then holds c for every channel.
+ * Needs K / bank to be a power of two (at most 256, at most 128 for bank 128). */
+enum { SQ_DYNAMIC = 0, SQ_STATIC = 1, SQ_DYNAMIC_TIED = 2 };
 enum { SQ_OUT_F32 = 0, SQ_OUT_BF16 = 1 };
 
 /* Problem description.  Section 4.1 writes a setting as B-(h_high/h_low)-s: here B = bank,
@@ -65,7 +73,7 @@ typedef struct {
   int32_t bank;      /* 32, 64 or 128 */
   int32_t topk;      /* high-precision channels per bank: a power of two, <= 32 and <= bank/2; dynamic mode also
                         >= bank/16 (the sparsities 1/2 ... 15/16 of Section 4.1); static mode: (K/bank)*topk % 32 == 0 */
-  int32_t mode;      /* SQ_DYNAMIC or SQ_STATIC */
+  int32_t mode;      /* SQ_DYNAMIC, SQ_STATIC or SQ_DYNAMIC_TIED */
   int32_t out_dtype; /* SQ_OUT_F32 or SQ_OUT_BF16 */
 } sq_params;
 
@@ -78,12 +86,14 @@ typedef struct {
                        bit (j % 32) of word j/32 set <=> channel j is high precision */
   float *scale_lo;  /* [M] per-token scale of the low part  (largest low magnitude / 7) */
   float *scale_hi;  /* [M] per-token scale of the high part (largest high magnitude / 127) */
-  int8_t *hi_dense; /* optional (may be NULL), dynamic mode only: [M, K] matrix-core-ready image of the high part,
+  int8_t *hi_dense; /* optional (may be NULL), dynamic modes only: [M, K] matrix-core-ready image of the high part,
                        a pure function of (hi_val, mask): the INT8 codes at their channels, 0 elsewhere, the 8
                        channels of every group stored even channels first, then odd channels (channel 8q+e sits
                        at byte 8q + 4*(e%2) + e/2).  sq_encode writes
                        it when the pointer is set; sq_gemm uses it when set and otherwise builds it in its
-                       workspace.  Not part of the format: a cache that saves sq_gemm one pass. */
+                       workspace.  Not part of the format: a cache that saves sq_gemm one pass.
+                       SQ_DYNAMIC_TIED: the same array holds the layer's single INT8 operand instead: the high
+                       codes at their channels and 16 * (low code) at the others, in the same byte order. */
 } sq_act;
 
 /* Plain INT4 weights with one fp32 scale per output channel. */
@@ -139,8 +149,9 @@ int sq_encode(const sq_params *p, const uint16_t *x_bf16, int64_t ldx, const uin
  *   a           encoded activations (static mode: a->mask is the [K/32] channel mask)
  *   w           weights
  *   y           device [M, ldy] fp32 or bf16 (p->out_dtype), ldy >= N (elements)
- *   acc_lo_dbg  optional device [M, N] int32: the exact low-part accumulators
- *   acc_hi_dbg  optional device [M, N] int32: the exact high-part accumulators
+ *   acc_lo_dbg  optional device [M, N] int32: the exact low-part accumulators (SQ_DYNAMIC_TIED: zeros)
+ *   acc_hi_dbg  optional device [M, N] int32: the exact high-part accumulators (SQ_DYNAMIC_TIED: the single
+ *               accumulator of the combined operand)
  *   workspace   device, sq_gemm_workspace_bytes(p) bytes, contents destroyed; may be NULL (size 0) when
  *               a->hi_dense is set or in static mode
  */

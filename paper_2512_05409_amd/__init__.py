@@ -15,7 +15,7 @@ from typing import Optional
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libsq.so")
 
-SQ_DYNAMIC, SQ_STATIC = 0, 1
+SQ_DYNAMIC, SQ_STATIC, SQ_DYNAMIC_TIED = 0, 1, 2
 SQ_OUT_F32, SQ_OUT_BF16 = 0, 1
 
 EXPORTS = (
@@ -173,11 +173,11 @@ class Act:
         nb = sq_act_bytes(p)
         self.p = p
         self.hi_dense = None
-        if with_hi_dense and p.mode == SQ_DYNAMIC:
+        if with_hi_dense and p.mode != SQ_STATIC:
             self.hi_dense = torch.empty(p.M * p.K, dtype=torch.int8, device=device)
         self.d_lo = torch.empty(nb.d_lo, dtype=torch.uint8, device=device)
         self.hi_val = torch.empty(nb.hi_val, dtype=torch.int8, device=device)
-        if p.mode == SQ_DYNAMIC:
+        if p.mode != SQ_STATIC:
             self.mask = torch.empty(nb.mask // 4, dtype=torch.int32, device=device)
         else:
             assert static_mask is not None and static_mask.numel() == p.K // 32

@@ -41,10 +41,11 @@ int check_params(const sq_params* p) {
   if (p->K % p->bank || p->K % 64 || p->K > 131072) return SQ_ERR_SHAPE;
   if (p->K / p->bank > 512) return SQ_ERR_SHAPE;
   if (p->M > (1 << 22) || p->N > (1 << 24)) return SQ_ERR_SHAPE;
-  if (p->mode != SQ_DYNAMIC && p->mode != SQ_STATIC) return SQ_ERR_UNSUPPORTED;
+  if (p->mode != SQ_DYNAMIC && p->mode != SQ_STATIC && p->mode != SQ_DYNAMIC_TIED) return SQ_ERR_UNSUPPORTED;
   if (p->out_dtype != SQ_OUT_F32 && p->out_dtype != SQ_OUT_BF16) return SQ_ERR_UNSUPPORTED;
   if (!pow2(p->topk) || p->topk > 32 || p->topk * 2 > p->bank) return SQ_ERR_UNSUPPORTED;
-  if (p->mode == SQ_DYNAMIC && p->topk * 16 < p->bank) return SQ_ERR_UNSUPPORTED;  // s in {1/2,3/4,7/8,15/16}
+  if (p->mode != SQ_STATIC && p->topk * 16 < p->bank) return SQ_ERR_UNSUPPORTED;  // s in {1/2,3/4,7/8,15/16}
+  if (p->mode == SQ_DYNAMIC_TIED && !sq::encode_stream_supports(*p)) return SQ_ERR_UNSUPPORTED;
   if (p->mode == SQ_STATIC && ((p->K / p->bank) * p->topk) % 32) return SQ_ERR_UNSUPPORTED;
   return SQ_OK;
 }
@@ -58,7 +59,7 @@ ActLayout act_layout(const sq_params* p) {
   ActLayout l;
   l.d_lo = static_cast<size_t>(p->M) * (p->K / 2);
   l.hi_val = static_cast<size_t>(p->M) * k_hi_of(p);
-  l.mask = p->mode == SQ_DYNAMIC ? static_cast<size_t>(p->M) * (p->K / 32) * 4 : static_cast<size_t>(p->K / 32) * 4;
+  l.mask = p->mode != SQ_STATIC ? static_cast<size_t>(p->M) * (p->K / 32) * 4 : static_cast<size_t>(p->K / 32) * 4;
   l.scale = static_cast<size_t>(p->M) * 4;
   l.total = l.d_lo + l.hi_val + l.mask + 2 * l.scale;
   return l;
@@ -110,7 +111,7 @@ size_t sq_act_bytes(const sq_params* p, size_t* d_lo, size_t* hi_val, size_t* ma
 
 size_t sq_gemm_workspace_bytes(const sq_params* p) {
   if (check_params(p) != SQ_OK) return 0;
-  if (p->mode == SQ_DYNAMIC) return align_up(static_cast<size_t>(p->M) * p->K, 256);
+  if (p->mode != SQ_STATIC) return align_up(static_cast<size_t>(p->M) * p->K, 256);
   return 16;
 }
 
@@ -118,7 +119,7 @@ size_t sq_linear_workspace_bytes(const sq_params* p) {
   if (check_params(p) != SQ_OK) return 0;
   const ActLayout l = act_layout(p);
   size_t t = align_up(l.d_lo, 256) + align_up(l.hi_val, 256) + 2 * align_up(l.scale, 256);
-  if (p->mode == SQ_DYNAMIC) t += align_up(l.mask, 256) + align_up(static_cast<size_t>(p->M) * p->K, 256);
+  if (p->mode != SQ_STATIC) t += align_up(l.mask, 256) + align_up(static_cast<size_t>(p->M) * p->K, 256);
   return t;
 }
 
@@ -195,6 +196,8 @@ int sq_encode(const sq_params* p, const uint16_t* x_bf16, int64_t ldx, const uin
   rc = check_act(p, out);
   if (rc != SQ_OK) return rc;
   if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
+  if (p->mode == SQ_DYNAMIC_TIED)
+    return sq::launch_encode_stream(*p, x_bf16, ldx, *out, out->hi_dense, true, 127.0f, 7.0f, static_cast<hipStream_t>(stream));
   return sq::launch_encode_dynamic(*p, x_bf16, ldx, *out, static_cast<hipStream_t>(stream));
 }
 
@@ -205,7 +208,7 @@ int sq_gemm(const sq_params* p, const sq_act* a, const sq_weight* w, void* y, in
   if ((rc = check_act(p, a)) != SQ_OK) return rc;
   if ((rc = check_weight(p, w)) != SQ_OK) return rc;
   if ((rc = check_y(p, y, ldy)) != SQ_OK) return rc;
-  const bool need_ws = p->mode == SQ_DYNAMIC && !a->hi_dense;
+  const bool need_ws = p->mode != SQ_STATIC && !a->hi_dense;
   if (need_ws && (!workspace || workspace_bytes < sq_gemm_workspace_bytes(p))) return SQ_ERR_WORKSPACE;
   if (need_ws && !aligned16(workspace)) return SQ_ERR_ALIGN;
   if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
@@ -226,13 +229,24 @@ int sq_gemm(const sq_params* p, const sq_act* a, const sq_weight* w, void* y, in
   g.out_bf16 = p->out_dtype == SQ_OUT_BF16;
   g.acc_lo_dbg = acc_lo_dbg;
   g.acc_hi_dbg = acc_hi_dbg;
-  if (p->mode == SQ_DYNAMIC) {
-    if (a->hi_dense) {
-      g.a_hi_dense = a->hi_dense;
-    } else {
+  if (p->mode != SQ_STATIC) {
+    const int8_t* image = a->hi_dense;
+    if (!image) {
       rc = sq::launch_expand_hi(*p, *a, static_cast<int8_t*>(workspace), st);
       if (rc != SQ_OK) return rc;
-      g.a_hi_dense = static_cast<const int8_t*>(workspace);
+      image = static_cast<const int8_t*>(workspace);
+    }
+    if (p->mode == SQ_DYNAMIC) {
+      g.a_hi_dense = image;
+    } else {
+      // tied scales: one product of the combined INT8 operand (stored in the order the plain weight rows
+      // unfold to) with the weights as they are, scaled by s_hi
+      g.a_lo = nullptr;
+      g.s_lo = nullptr;
+      g.K_hi = p->K;
+      g.a_hi_compact = image;
+      g.lda_hi_compact = p->K;
+      g.w_hi = w->wq;
     }
   } else {
     g.K_hi = k_hi_of(p);
@@ -265,7 +279,7 @@ int sq_linear(const sq_params* p, const uint16_t* x_bf16, int64_t ldx, const uin
   a.scale_hi = reinterpret_cast<float*>(ws);
   ws += align_up(l.scale, 256);
   a.hi_dense = nullptr;
-  if (p->mode == SQ_DYNAMIC) {
+  if (p->mode != SQ_STATIC) {
     a.mask = reinterpret_cast<uint32_t*>(ws);
     ws += align_up(l.mask, 256);
     a.hi_dense = reinterpret_cast<int8_t*>(ws);

@@ -259,8 +259,10 @@ __global__ __launch_bounds__(MAXT) void encode_static_kernel(const uint16_t* __r
 // (hi_val, mask) -> zero-padded INT8 image of the high part.  Inside every group of 8 channels the
 // bytes are stored even channels first, then odd channels: the order in which the GEMM kernel's
 // nibble widening delivers a weight row.
+// d_lo != nullptr (tied scales): the other bytes hold 16 x the low codes instead of zeros.
 __global__ __launch_bounds__(256) void expand_hi_kernel(const int8_t* __restrict__ hi_val,
-                                                        const uint32_t* __restrict__ mask, int64_t total, int K,
+                                                        const uint32_t* __restrict__ mask,
+                                                        const uint8_t* __restrict__ d_lo, int64_t total, int K,
                                                         int B, int KT, int8_t* __restrict__ out) {
   __shared__ uint4 stage[256 * 2];
   const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
@@ -278,6 +280,11 @@ __global__ __launch_bounds__(256) void expand_hi_kernel(const int8_t* __restrict
   uint4* my = stage + threadIdx.x * 2;
   my[0] = make_uint4(0, 0, 0, 0);
   my[1] = make_uint4(0, 0, 0, 0);
+  if (d_lo) {  // a nibble moved to the high half of its byte is 16 x the code
+    const uint4 d = *reinterpret_cast<const uint4*>(d_lo + row * (K / 2) + static_cast<int64_t>(wg) * 16);
+    my[0] = make_uint4((d.x << 4) & 0xF0F0F0F0u, d.x & 0xF0F0F0F0u, (d.y << 4) & 0xF0F0F0F0u, d.y & 0xF0F0F0F0u);
+    my[1] = make_uint4((d.z << 4) & 0xF0F0F0F0u, d.z & 0xF0F0F0F0u, (d.w << 4) & 0xF0F0F0F0u, d.w & 0xF0F0F0F0u);
+  }
   int8_t* myb = reinterpret_cast<int8_t*>(my);
   int left = KT - rank;  // never read past the bank's codes, whatever the mask holds
   while (word && left > 0) {
@@ -417,8 +424,8 @@ int launch_encode_static(const sq_params& p, const uint16_t* x, int64_t ldx, con
 int launch_expand_hi(const sq_params& p, const sq_act& a, int8_t* s_hi_dense, hipStream_t st) {
   const int64_t total = static_cast<int64_t>(p.M) * (p.K / 32);
   const int64_t blocks = (total + 255) / 256;
-  hipLaunchKernelGGL(expand_hi_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, a.hi_val, a.mask, total,
-                     p.K, p.bank, p.topk, s_hi_dense);
+  hipLaunchKernelGGL(expand_hi_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, a.hi_val, a.mask,
+                     p.mode == SQ_DYNAMIC_TIED ? a.d_lo : nullptr, total, p.K, p.bank, p.topk, s_hi_dense);
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 

@@ -49,7 +49,7 @@ class GuardedAct(sq.Act):
         self.g_shi = Guarded(nb.scale, torch.float32)
         self.d_lo, self.hi_val = self.g_d_lo.t, self.g_hi.t
         self.scale_lo, self.scale_hi = self.g_slo.t, self.g_shi.t
-        if p.mode == sq.SQ_DYNAMIC:
+        if p.mode != sq.SQ_STATIC:
             self.g_mask = Guarded(nb.mask, torch.int32)
             self.mask = self.g_mask.t
         else:
@@ -71,7 +71,7 @@ def assert_encoding_equal(act: sq.Act, enc, rows=None):
     s_lo = act.scale_lo.cpu().numpy().view(np.uint32)
     s_hi = act.scale_hi.cpu().numpy().view(np.uint32)
     sel = slice(None) if rows is None else rows
-    if p.mode == sq.SQ_DYNAMIC:
+    if p.mode != sq.SQ_STATIC:
         mask = act.mask.cpu().numpy().view(np.uint32).reshape(p.M, p.K // 32)
         bad = np.flatnonzero((mask[sel] != enc.mask).any(1))
         assert bad.size == 0, f"mask differs in rows {bad[:8]}"

@@ -72,7 +72,9 @@ def _encode(L, p, x=FAKE, ldx=None, mask=None, act=None):
     (dict(K=32768, bank=32), -2),       # more than 512 banks per row
     (dict(bank=48), -3), (dict(bank=256), -3),
     (dict(topk=0), -3), (dict(topk=3), -3), (dict(topk=64, bank=128), -3), (dict(topk=2, bank=64), -3),
-    (dict(mode=2), -3), (dict(out_dtype=5), -3),
+    (dict(mode=3), -3), (dict(out_dtype=5), -3),
+    (dict(mode=2, K=64 * 5), -3),       # tied scales: K / bank must be a power of two
+    (dict(mode=2, K=32768, bank=64), -3),  # tied scales: at most 256 banks per row
     (dict(mode=1, K=64 * 5, bank=64, topk=4), -3),   # static: compact high width not a multiple of 32
 ])
 def test_bad_params_are_refused(L, kw, code):
