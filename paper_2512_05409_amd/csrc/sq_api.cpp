@@ -96,7 +96,7 @@ int sq_init(void) { return sq::ensure_device_ready(); }
 
 const char* sq_gemm_variant(const sq_params* p) {
   if (check_params(p) != SQ_OK) return "invalid";
-  return sq::gemm_variant_name(p->M, p->N, p->K, p->mode == SQ_DYNAMIC);
+  return sq::gemm_variant_name(p->M, p->N, p->K, p->mode == SQ_DYNAMIC, p->mode == SQ_DYNAMIC_TIED);
 }
 
 size_t sq_act_bytes(const sq_params* p, size_t* d_lo, size_t* hi_val, size_t* mask, size_t* scale) {

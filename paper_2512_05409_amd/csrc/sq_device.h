@@ -62,7 +62,8 @@ struct GemmArgs {
   int32_t* acc_hi_dbg;
 };
 int launch_gemm(const GemmArgs& g, hipStream_t st);
-// Name of the kernel variant launch_gemm picks for a shape ("tile128x256", "tile128x128", "tile64x64", "stream32").
-const char* gemm_variant_name(int M, int N, int K, bool dynamic);
+// Name of the kernel variant launch_gemm picks for a shape ("tile256x256", "tile128x256", "tile128x128",
+// "tile64x64", "stream32").  dynamic: two products in one loop; single: one product (tied scales, plain W4A8).
+const char* gemm_variant_name(int M, int N, int K, bool dynamic, bool single);
 
 }  // namespace sq

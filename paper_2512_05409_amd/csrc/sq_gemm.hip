@@ -27,9 +27,15 @@ namespace {
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 constexpr int KS = 128;  // channels per K step
+#ifndef SQ_HUGE_MIN_TILES
+#define SQ_HUGE_MIN_TILES 512
+#endif
+constexpr int kHugeMinTiles = SQ_HUGE_MIN_TILES;  // 256x256 tiles a single-product shape needs to use them
 constexpr int NT = 256;  // threads per workgroup
 
-template <int BM_, int BN_>
+// WITH_LO = false: a tile for loops without a packed low operand (the single-product modes), whose stage
+// holds no room for one; that is what lets 256 tokens x 256 channels fit three stages into LDS.
+template <int BM_, int BN_, bool WITH_LO = true>
 struct Tile {
   static constexpr int BM = BM_;              // tokens per workgroup
   static constexpr int BN = BN_;              // output channels per workgroup
@@ -38,7 +44,7 @@ struct Tile {
   static constexpr int TI = WM / 32;          // 32-row tiles per wave along M
   static constexpr int TJ = WN / 32;          // along N
   static constexpr int A_LO = 0;              // [BM][64 B]   packed INT4
-  static constexpr int A_HI = BM * 64;        // [BM][128 B]  INT8
+  static constexpr int A_HI = WITH_LO ? BM * 64 : 0;  // [BM][128 B]  INT8
   static constexpr int B_OFF = A_HI + BM * 128;  // [BN][64 B] packed INT4
   static constexpr int STAGE = B_OFF + BN * 64;
   static constexpr int LDS_BYTES = 3 * STAGE;
@@ -385,10 +391,11 @@ __device__ __forceinline__ void epilogue_typed(const GemmArgs& g, const EpiScale
   constexpr int PER16 = 16 / ESZ;         // outputs per 16-byte store
   constexpr int CHUNKS = T::WN / PER16;   // 16-byte chunks per row
   constexpr int ROWS_PER_PASS = 64 / CHUNKS;
-  static_assert(1024 + 4 * 32 * ROW <= T::LDS_BYTES, "transposition buffers must fit in the stage memory");
+  constexpr int SC_BYTES = 2 * T::BM * 4;  // [0, BM): s_lo, [BM, 2 BM): s_hi
+  static_assert(SC_BYTES + 4 * 32 * ROW <= T::LDS_BYTES, "transposition buffers must fit in the stage memory");
   const int tid = threadIdx.x;
-  float* sc = reinterpret_cast<float*>(lds);  // [0, BM): s_lo, [BM, 2 BM): s_hi   (BM <= 128)
-  char* tb = lds + 1024 + wave * (32 * ROW);
+  float* sc = reinterpret_cast<float*>(lds);
+  char* tb = lds + SC_BYTES + wave * (32 * ROW);
   if (tid < T::BM) {
     sc[tid] = es.slo;
     sc[T::BM + tid] = es.shi;
@@ -862,12 +869,19 @@ typedef Tile<64, 64> Skinny;  // M <= 64 (decode): bound by streaming the INT4 w
                               // tile is narrow in N to spread the weight rows over every compute unit
                               // (several small workgroups per unit keep enough loads in flight)
 typedef Tile<128, 128> Mid;   // shapes with too few 128x256 tiles to occupy every compute unit
+typedef Tile<256, 256, false> Huge;  // single-product modes on large shapes: with one accumulator set a wave
+                                     // holds 128 x 128 outputs, which halves the operand traffic and the
+                                     // widening arithmetic per matrix instruction and doubles the matrix
+                                     // instructions between two barriers to 64, as in the two-product loop
 
-enum Variant { V_BIG, V_MID, V_SMALL, V_STREAM };
+enum Variant { V_BIG, V_MID, V_SMALL, V_STREAM, V_HUGE };
 
-// Which kernel a shape runs on.  dynamic: the call has the low operand and the zero-padded high image.
-Variant pick_variant(int M, int N, int K, bool dynamic) {
+// Which kernel a shape runs on.  dynamic: the call has the low operand and the zero-padded high image;
+// single: one product only (tied scales, plain W4A8).
+Variant pick_variant(int M, int N, int K, bool dynamic, bool single) {
   if (M <= 64) return (dynamic && M <= 32 && K % KS == 0) ? V_STREAM : V_SMALL;
+  const int64_t huge_tiles = static_cast<int64_t>((M + 255) / 256) * ((N + 255) / 256);
+  if (single && huge_tiles >= kHugeMinTiles) return V_HUGE;
   const int64_t big_tiles = static_cast<int64_t>((M + 127) / 128) * ((N + 255) / 256);
   return big_tiles <= 128 ? V_MID : V_BIG;  // then twice as many half-size tiles still run in one round
 }
@@ -880,6 +894,9 @@ hipError_t raise_lds_limit() {
 
 template <int MODE>
 int launch_for_mode(const GemmArgs& g, hipStream_t st, Variant v) {
+  if constexpr (MODE == 2) {
+    if (v == V_HUGE) return launch_mode<Huge, 2>(g, st);
+  }
   if (v == V_BIG) return launch_mode<Big, MODE>(g, st);
   if (v == V_MID) return launch_mode<Mid, MODE>(g, st);
   return launch_mode<Skinny, MODE>(g, st);
@@ -897,14 +914,16 @@ int init_gemm_kernels() {
   if (e == hipSuccess) e = raise_lds_limit<T, 2>();
   SQ_RAISE(Big) SQ_RAISE(Mid) SQ_RAISE(Skinny)
 #undef SQ_RAISE
+  if (e == hipSuccess) e = raise_lds_limit<Huge, 2>();
   if (e == hipSuccess)
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_skinny_kernel<1>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, SkinnyCfg<1>::LDS_BYTES);
   return e == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
-const char* gemm_variant_name(int M, int N, int K, bool dynamic) {
-  switch (pick_variant(M, N, K, dynamic)) {
+const char* gemm_variant_name(int M, int N, int K, bool dynamic, bool single) {
+  switch (pick_variant(M, N, K, dynamic, single)) {
+    case V_HUGE: return "tile256x256";
     case V_BIG: return "tile128x256";
     case V_MID: return "tile128x128";
     case V_SMALL: return "tile64x64";
@@ -914,7 +933,7 @@ const char* gemm_variant_name(int M, int N, int K, bool dynamic) {
 
 int launch_gemm(const GemmArgs& g, hipStream_t st) {
   const bool dynamic = g.a_lo && g.a_hi_dense;
-  const Variant v = pick_variant(g.M, g.N, g.K, dynamic);
+  const Variant v = pick_variant(g.M, g.N, g.K, dynamic, !g.a_lo);
   if (dynamic) {
     if (v == V_STREAM) return launch_skinny<1>(g, st);
     return launch_for_mode<0>(g, st, v);

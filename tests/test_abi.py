@@ -178,3 +178,6 @@ def test_gemm_variant_names(L):
     assert sq.sq_gemm_variant(sq.params(8, 8192 + 64, 28672)) == "tile64x64"      # K % 128 != 0
     assert sq.sq_gemm_variant(sq.params(8, 8192, 28672, mode=sq.SQ_STATIC)) == "tile64x64"
     assert sq.sq_gemm_variant(sq.params(8, 100, 64)) == "invalid"
+    assert sq.sq_gemm_variant(sq.params(4096, 4096, 22016, mode=sq.SQ_DYNAMIC_TIED)) == "tile256x256"   # 16 x 86 tiles
+    assert sq.sq_gemm_variant(sq.params(1500, 512, 6100, mode=sq.SQ_DYNAMIC_TIED)) == "tile128x256"
+    assert sq.sq_gemm_variant(sq.params(8, 8192, 28672, mode=sq.SQ_DYNAMIC_TIED)) == "tile64x64"

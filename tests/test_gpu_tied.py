@@ -146,3 +146,45 @@ def test_tied_at_the_benchmark_shape():
     sq.sq_linear(p, xd, sq.weight(wqd, swd), y2, ws)
     torch.cuda.synchronize()
     assert torch.equal(y, y2)
+
+
+@pytest.mark.parametrize("M,K,N", [(4100, 256, 8200), (4353, 1024, 7950)])
+def test_huge_tile_single_product_every_element(M, K, N):
+    """The 256 x 256 tile of the single-product modes (at least 512 such tiles): tied-scale layer and the plain
+    W4A8 reference, every element.  Expected accumulators: float64 BLAS matmul of the oracle's integer codes
+    (exact below 2^53); the epilogue's two fp32 multiplications written out in numpy; sampled rows also through
+    the oracle's own product."""
+    bank, topk = 64, 8
+    p = sq.params(M, K, N, bank, topk, mode=sq.SQ_DYNAMIC_TIED, out_dtype=sq.SQ_OUT_F32)
+    assert sq.sq_gemm_variant(p) == "tile256x256"
+    _say(f"huge tile tied M={M} K={K} N={N}")
+    bits, wq, sw = random_case(1700 + M + K + N, M, K, N, outliers=4)
+    enc = oracle.encode_tied(bits, bank, topk)
+    W = workloads.unpack_int4(wq).astype(np.float64)
+    acc_want = (enc.codes.astype(np.float64) @ W.T).astype(np.int64)
+    y_want = ((acc_want.astype(np.float32) * enc.s_hi[:, None]).astype(np.float32) * sw[None, :]).astype(np.float32)
+    y, acc = run_gemm_tied(p, enc, wq, sw, sq.SQ_OUT_F32, True)
+    assert np.array_equal(acc.astype(np.int64), acc_want)
+    assert np.array_equal(y.view(np.uint32), y_want.view(np.uint32))
+    rows = np.array([0, 255, 256, M // 2, M - 1])
+    sub = oracle.tied.EncodedTied(len(rows), K, bank, topk, None, None, None, enc.s_lo[rows], enc.s_hi[rows], enc.codes[rows])
+    prod = oracle.gemm_tied(sub, wq, sw)
+    assert np.array_equal(y[rows].view(np.uint32), prod.y32.view(np.uint32)) and np.array_equal(acc[rows], prod.acc)
+    y16, _ = run_gemm_tied(p, enc, wq, sw, sq.SQ_OUT_BF16, True)
+    assert np.array_equal(y16, workloads.f32_to_bf16_bits(y_want))
+    # plain W4A8 reference on the same tile
+    _say("huge tile dense w4a8")
+    rng = np.random.default_rng(M + N)
+    a = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    sa = rng.uniform(0.01, 0.1, M).astype(np.float32)
+    pd = sq.params(M, K, N, out_dtype=sq.SQ_OUT_F32)
+    wqd, swd = dev(wq), dev(sw)
+    pre = torch.empty(N * K // 2, dtype=torch.uint8, device="cuda")
+    sq.sq_dense_w4a8_prepack(pd, wqd, pre)
+    yd = Guarded(M * N * 4, torch.float32)
+    sq.sq_dense_w4a8_gemm(pd, dev(a), dev(sa), sq.weight(wqd, swd, pre), yd.t)
+    torch.cuda.synchronize()
+    yd.check()
+    accd = (a.astype(np.float64) @ W.T).astype(np.int64)
+    want = (accd.astype(np.float32) * sa[:, None]).astype(np.float32) * sw[None, :]
+    assert np.array_equal(yd.host(np.float32).reshape(M, N), want.astype(np.float32))
