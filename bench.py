@@ -209,9 +209,12 @@ def main():
                        "algorithmic_bytes": cal_bytes, "achieved": cal_bytes / (cal_ms * 1e-3) / 1e9,
                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": cal_bytes / (cal_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                        "calibration_tokens": T, "note": "inputs not rotated: partly served from the Infinity Cache"}
-        mask = md.cpu().numpy().view(np.uint32)
+        # the weights are reordered by the mask on the device, from the device copy of the mask alone
         pre = torch.empty(sq.sq_weight_prepack_bytes(p), dtype=torch.uint8, device="cuda")
-        sq.sq_weight_prepack(p, wqd, mask, md, pre)
+        bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+        sq.sq_weight_prepack(p, wqd, None, md, pre, bad_banks=bad)
+        torch.cuda.synchronize()
+        assert int(bad.item()) == 0, "calibration produced a malformed mask"
     w = sq.weight(wqd, swd, pre)
     # Few tokens: the GEMM streams the weights once and is HBM-bound (the ridge of INT8 MFMA against HBM is near
     # M = 157), so the weights rotate over copies that together exceed the 256 MB Infinity Cache as well.
@@ -229,7 +232,10 @@ def main():
     xs = [x0] + [x0.clone() for _ in range(n_x - 1)]
     n_y = 2
     ys = [torch.empty(M * N, dtype=torch.int16, device="cuda") for _ in range(n_y)]
-    acts = [sq.Act(p, static_mask=md, with_hi_dense=True) for _ in range(2)]
+    acts = [sq.Act(p, static_mask=md, with_hi_dense=True, with_lo_compact=True) for _ in range(2)]
+    if static:
+        for a_ in acts:
+            a_.d_lo = None  # as in sq_linear: only the reordered low part is produced and multiplied
 
     def step(i, ev=None):
         a = acts[i % 2]
@@ -271,10 +277,11 @@ def main():
 
     # Algorithmic work of the dominant kernel (the GEMM): both products the layer is defined with.
     alg_ops = 2.0 * M * N * K * (1.0 + k / b)
-    issued_ops = 2.0 * M * N * K * (1.0 + (k / b if static else 1.0))  # dynamic: the high pass is zero-padded to dense
+    # dynamic: the high pass is zero-padded to dense; static: both operands reordered, low pass over K - K_hi
+    issued_ops = 2.0 * M * N * K * (1.0 if static else 2.0)
     gemm_s = float(gemm_ms.mean()) * 1e-3
     enc_s = float(enc_ms.mean()) * 1e-3
-    enc_bytes = M * K * 2 + M * K // 2 + M * (K // b) * k + (0 if static else M * K // 8) + 8 * M
+    enc_bytes = M * K * 2 + (M * (K - (K // b) * k) // 2 if static else M * K // 2) + M * (K // b) * k + (0 if static else M * K // 8) + 8 * M
     enc_bytes_written_extra = 0 if static else M * K  # the matrix-core-ready image of the high part
     # what one GEMM launch has to move at least: the encoded activations, the weights, the scales, the output
     gemm_bytes = (M * K // 2 + M * (K // b) * k + (0 if static else M * K // 8) + 8 * M

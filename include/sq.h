@@ -94,13 +94,20 @@ typedef struct {
                        workspace.  Not part of the format: a cache that saves sq_gemm one pass.
                        SQ_DYNAMIC_TIED: the same array holds the layer's single INT8 operand instead: the high
                        codes at their channels and 16 * (low code) at the others, in the same byte order. */
+  uint8_t *lo_compact; /* optional (may be NULL), static mode only: [M, K_lo/2], K_lo = K - (K/bank)*topk: the low
+                       codes of the low channels only, ascending channel order, two per byte -- the activations
+                       "selected and gathered" by the mask (Section 3.3), the operand that goes with the reordered
+                       weights of sq_weight_prepack.  A pure function of (d_lo, mask).  sq_encode writes it when the
+                       pointer is set (K <= 65535 and K <= about 37000 so that a row fits in LDS; otherwise
+                       SQ_ERR_UNSUPPORTED); then d_lo may be NULL.  sq_gemm multiplies it when set (the low
+                       product then runs over K_lo channels) and d_lo otherwise (over K). */
 } sq_act;
 
 /* Plain INT4 weights with one fp32 scale per output channel. */
 typedef struct {
   const uint8_t *wq;      /* [N, K/2]  same nibble order as d_lo, values in [-8, 7] */
   const float *scale;     /* [N] */
-  const void *prepacked;  /* static mode: output of sq_weight_prepack (required); dynamic mode: ignored, may be NULL */
+  const void *prepacked;  /* static mode: output of sq_weight_prepack (required); dynamic modes: ignored, may be NULL */
 } sq_weight;
 
 /* Per-device initialisation for the current device (idempotent, thread-safe): raises the kernels' dynamic-LDS
@@ -116,29 +123,40 @@ size_t sq_act_bytes(const sq_params *p, size_t *d_lo, size_t *hi_val, size_t *ma
  * high part, M*K bytes; static: none -> returns 16 so that a valid pointer can always be passed). */
 size_t sq_gemm_workspace_bytes(const sq_params *p);
 
-/* Bytes of device workspace sq_linear needs: an sq_act including hi_dense. */
+/* Bytes of device workspace sq_linear needs: the encoded activations in the form sq_gemm multiplies
+ * (dynamic modes: an sq_act with hi_dense; static mode: lo_compact, hi_val and the scales). */
 size_t sq_linear_workspace_bytes(const sq_params *p);
 
-/* Bytes of the prepacked weight image for the static mode (0 in dynamic mode). */
+/* Bytes of sq_act::lo_compact for these parameters (static mode; 0 otherwise). */
+size_t sq_lo_compact_bytes(const sq_params *p);
+
+/* Bytes of the reordered weight image for the static mode, N*K/2 (0 in the dynamic modes). */
 size_t sq_weight_prepack_bytes(const sq_params *p);
 
 /*
  * Static mode only (Algorithm 2, last step: the weights are reordered by the mask so that the
- * kernels only select and gather on the activation side, Section 3.3): gathers the weight
- * columns of the high channels into a compact [N, (K/bank)*topk / 2] INT4 image.
+ * kernels only select and gather on the activation side, Section 3.3): the weight columns are
+ * reordered so that the high channels are contiguous and the low channels are contiguous:
+ *   out = [ N x K_hi/2 bytes: columns of the high channels | N x K_lo/2 bytes: columns of the low channels ],
+ * K_hi = (K/bank)*topk, K_lo = K - K_hi, ascending channel order in both (the orders of hi_val and lo_compact).
  *   wq               device [N, K/2]
- *   static_mask_host HOST   [K/32]; checked here: every bank must hold exactly topk bits (SQ_ERR_MASK)
- *   static_mask      device [K/32], same content
+ *   static_mask_host HOST   [K/32], or NULL.  When given it is checked here: every bank must hold exactly
+ *                    topk bits (SQ_ERR_MASK, nothing is launched)
+ *   static_mask      device [K/32] (same content as the host copy when there is one): everything on the
+ *                    device is done from this one, so a mask produced by sq_calibrate_static needs no host copy
  *   out              device, sq_weight_prepack_bytes(p) bytes
+ *   bad_banks        device int32, or NULL: receives the number of banks of static_mask that do not hold
+ *                    exactly topk bits (0 for a valid mask); an image built from a malformed mask is unusable
  */
 int sq_weight_prepack(const sq_params *p, const uint8_t *wq, const uint32_t *static_mask_host,
-                      const uint32_t *static_mask, void *out, void *stream);
+                      const uint32_t *static_mask, void *out, int32_t *bad_banks, void *stream);
 
 /*
  * X -> SQ-format (Eq. (1); selection rule of Sections 3.2.2 / 4.3 or Algorithm 2's mask).
  *   x_bf16       device [M, ldx] bf16 bit patterns, ldx >= K (elements)
  *   static_mask  device [K/32] in static mode (also stored by the caller in out->mask), NULL in dynamic mode
- *   out          arrays sized by sq_act_bytes; in static mode out->mask is not written
+ *   out          arrays sized by sq_act_bytes; in static mode out->mask is not written, and out->d_lo may be NULL
+ *                when out->lo_compact is set
  * Ties in magnitude go to the lower channel; codes are round-half-even of x * (Q / amax).
  */
 int sq_encode(const sq_params *p, const uint16_t *x_bf16, int64_t ldx, const uint32_t *static_mask,

@@ -22,7 +22,7 @@ EXPORTS = (
     "sq_act_bytes", "sq_gemm_workspace_bytes", "sq_linear_workspace_bytes", "sq_weight_prepack_bytes",
     "sq_weight_prepack", "sq_encode", "sq_gemm", "sq_linear", "sq_dense_w4a8_prepack", "sq_dense_w4a8_gemm",
     "sq_calibrate_workspace_bytes", "sq_calibrate_static", "sq_probe_mfma_i8", "sq_probe_stream", "sq_status_string", "sq_version",
-    "sq_init", "sq_gemm_variant", "sq_linear_noalloc",
+    "sq_init", "sq_gemm_variant", "sq_linear_noalloc", "sq_lo_compact_bytes",
 )
 SQ_NOALLOC_SCRATCH_BYTES = 8 << 20
 
@@ -40,7 +40,8 @@ class sq_params(ctypes.Structure):
 
 class sq_act(ctypes.Structure):
     _fields_ = [("d_lo", ctypes.c_void_p), ("hi_val", ctypes.c_void_p), ("mask", ctypes.c_void_p),
-                ("scale_lo", ctypes.c_void_p), ("scale_hi", ctypes.c_void_p), ("hi_dense", ctypes.c_void_p)]
+                ("scale_lo", ctypes.c_void_p), ("scale_hi", ctypes.c_void_p), ("hi_dense", ctypes.c_void_p),
+                ("lo_compact", ctypes.c_void_p)]
 
 
 class sq_weight(ctypes.Structure):
@@ -60,10 +61,10 @@ def lib() -> ctypes.CDLL:
         P, vp, sz, i64 = ctypes.POINTER, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int64
         L.sq_act_bytes.argtypes = [P(sq_params), P(sz), P(sz), P(sz), P(sz)]
         L.sq_act_bytes.restype = sz
-        for f in (L.sq_gemm_workspace_bytes, L.sq_linear_workspace_bytes, L.sq_weight_prepack_bytes):
+        for f in (L.sq_gemm_workspace_bytes, L.sq_linear_workspace_bytes, L.sq_weight_prepack_bytes, L.sq_lo_compact_bytes):
             f.argtypes = [P(sq_params)]
             f.restype = sz
-        L.sq_weight_prepack.argtypes = [P(sq_params), vp, vp, vp, vp, vp]
+        L.sq_weight_prepack.argtypes = [P(sq_params), vp, vp, vp, vp, vp, vp]
         L.sq_encode.argtypes = [P(sq_params), vp, i64, vp, P(sq_act), vp]
         L.sq_gemm.argtypes = [P(sq_params), P(sq_act), P(sq_weight), vp, i64, vp, vp, vp, sz, vp]
         L.sq_linear.argtypes = [P(sq_params), vp, i64, vp, P(sq_weight), vp, i64, vp, sz, vp]
@@ -164,15 +165,22 @@ def sq_weight_prepack_bytes(p: sq_params) -> int:
     return int(lib().sq_weight_prepack_bytes(ctypes.byref(p)))
 
 
+def sq_lo_compact_bytes(p: sq_params) -> int:
+    return int(lib().sq_lo_compact_bytes(ctypes.byref(p)))
+
+
 class Act:
     """Device buffers of one SQ-format activation matrix (torch tensors, caller-visible)."""
 
-    def __init__(self, p: sq_params, device="cuda", static_mask=None, with_hi_dense=False):
+    def __init__(self, p: sq_params, device="cuda", static_mask=None, with_hi_dense=False, with_lo_compact=False):
         import torch
 
         nb = sq_act_bytes(p)
         self.p = p
         self.hi_dense = None
+        self.lo_compact = None
+        if with_lo_compact and p.mode == SQ_STATIC:
+            self.lo_compact = torch.empty(sq_lo_compact_bytes(p), dtype=torch.uint8, device=device)
         if with_hi_dense and p.mode != SQ_STATIC:
             self.hi_dense = torch.empty(p.M * p.K, dtype=torch.int8, device=device)
         self.d_lo = torch.empty(nb.d_lo, dtype=torch.uint8, device=device)
@@ -187,20 +195,20 @@ class Act:
 
     def c(self) -> sq_act:
         return sq_act(_ptr(self.d_lo), _ptr(self.hi_val), _ptr(self.mask), _ptr(self.scale_lo), _ptr(self.scale_hi),
-                      _ptr(getattr(self, "hi_dense", None)))
+                      _ptr(getattr(self, "hi_dense", None)), _ptr(getattr(self, "lo_compact", None)))
 
 
 def weight(wq, scale, prepacked=None) -> sq_weight:
     return sq_weight(_ptr(wq), _ptr(scale), _ptr(prepacked))
 
 
-def sq_weight_prepack(p: sq_params, wq, static_mask_host, static_mask, out, stream=None) -> None:
-    """static_mask_host: numpy uint32 [K/32] (host); the rest are device tensors."""
+def sq_weight_prepack(p: sq_params, wq, static_mask_host, static_mask, out, bad_banks=None, stream=None) -> None:
+    """static_mask_host: numpy uint32 [K/32] (host) or None; the rest are device tensors (bad_banks: int32[1] or None)."""
     import numpy as np
 
-    mh = np.ascontiguousarray(static_mask_host, dtype=np.uint32)
-    _check(lib().sq_weight_prepack(ctypes.byref(p), _ptr(wq), mh.ctypes.data, _ptr(static_mask), _ptr(out),
-                                   _stream(stream)), "sq_weight_prepack")
+    mh = None if static_mask_host is None else np.ascontiguousarray(static_mask_host, dtype=np.uint32)
+    _check(lib().sq_weight_prepack(ctypes.byref(p), _ptr(wq), None if mh is None else mh.ctypes.data, _ptr(static_mask),
+                                   _ptr(out), _ptr(bad_banks), _stream(stream)), "sq_weight_prepack")
 
 
 def sq_encode(p: sq_params, x_bf16, out: Act, static_mask=None, ldx: Optional[int] = None, stream=None) -> None:

@@ -51,6 +51,7 @@ int check_params(const sq_params* p) {
 }
 
 inline int k_hi_of(const sq_params* p) { return (p->K / p->bank) * p->topk; }
+inline size_t lo_compact_bytes(const sq_params* p) { return static_cast<size_t>(p->M) * ((p->K - k_hi_of(p)) / 2); }
 
 struct ActLayout {
   size_t d_lo, hi_val, mask, scale, total;
@@ -66,11 +67,11 @@ ActLayout act_layout(const sq_params* p) {
 }
 
 int check_act(const sq_params* p, const sq_act* a) {
-  if (!a || !a->d_lo || !a->hi_val || !a->mask || !a->scale_lo || !a->scale_hi) return SQ_ERR_NULL;
+  if (!a || !a->hi_val || !a->mask || !a->scale_lo || !a->scale_hi) return SQ_ERR_NULL;
+  if (!a->d_lo && !(p->mode == SQ_STATIC && a->lo_compact)) return SQ_ERR_NULL;
   if (!aligned16(a->d_lo) || !aligned16(a->hi_val) || !aligned16(a->mask) || !aligned16(a->scale_lo) ||
-      !aligned16(a->scale_hi) || !aligned16(a->hi_dense))
+      !aligned16(a->scale_hi) || !aligned16(a->hi_dense) || !aligned16(a->lo_compact))
     return SQ_ERR_ALIGN;
-  (void)p;
   return SQ_OK;
 }
 
@@ -115,27 +116,33 @@ size_t sq_gemm_workspace_bytes(const sq_params* p) {
   return 16;
 }
 
+size_t sq_lo_compact_bytes(const sq_params* p) {
+  if (check_params(p) != SQ_OK || p->mode != SQ_STATIC) return 0;
+  return lo_compact_bytes(p);
+}
+
 size_t sq_linear_workspace_bytes(const sq_params* p) {
   if (check_params(p) != SQ_OK) return 0;
   const ActLayout l = act_layout(p);
-  size_t t = align_up(l.d_lo, 256) + align_up(l.hi_val, 256) + 2 * align_up(l.scale, 256);
+  const bool compact = p->mode == SQ_STATIC && sq::encode_static_gather_supports(*p);
+  size_t t = align_up(compact ? lo_compact_bytes(p) : l.d_lo, 256) + align_up(l.hi_val, 256) + 2 * align_up(l.scale, 256);
   if (p->mode != SQ_STATIC) t += align_up(l.mask, 256) + align_up(static_cast<size_t>(p->M) * p->K, 256);
   return t;
 }
 
 size_t sq_weight_prepack_bytes(const sq_params* p) {
   if (check_params(p) != SQ_OK || p->mode != SQ_STATIC) return 0;
-  return static_cast<size_t>(p->N) * (k_hi_of(p) / 2);
+  return static_cast<size_t>(p->N) * (p->K / 2);
 }
 
 int sq_weight_prepack(const sq_params* p, const uint8_t* wq, const uint32_t* static_mask_host,
-                      const uint32_t* static_mask, void* out, void* stream) {
+                      const uint32_t* static_mask, void* out, int32_t* bad_banks, void* stream) {
   int rc = check_params(p);
   if (rc != SQ_OK) return rc;
   if (p->mode != SQ_STATIC) return SQ_ERR_UNSUPPORTED;
-  if (!wq || !static_mask_host || !static_mask || !out) return SQ_ERR_NULL;
-  if (!aligned16(wq) || !aligned16(out)) return SQ_ERR_ALIGN;
-  for (int g = 0; g < p->K / p->bank; ++g) {
+  if (!wq || !static_mask || !out) return SQ_ERR_NULL;
+  if (!aligned16(wq) || !aligned16(out) || !aligned16(static_mask)) return SQ_ERR_ALIGN;
+  for (int g = 0; static_mask_host && g < p->K / p->bank; ++g) {
     int c = 0;
     for (int i = 0; i < p->bank; ++i) {
       const int j = g * p->bank + i;
@@ -144,8 +151,13 @@ int sq_weight_prepack(const sq_params* p, const uint8_t* wq, const uint32_t* sta
     if (c != p->topk) return SQ_ERR_MASK;
   }
   if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
-  return sq::launch_weight_prepack(p->N, p->K, p->bank, p->topk, k_hi_of(p), wq, static_mask,
-                                   static_cast<uint8_t*>(out), static_cast<hipStream_t>(stream));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (bad_banks && (rc = sq::launch_mask_check(p->K, p->bank, p->topk, static_mask, bad_banks, st)) != SQ_OK) return rc;
+  uint8_t* o = static_cast<uint8_t*>(out);
+  rc = sq::launch_weight_prepack(p->N, p->K, p->bank, p->topk, k_hi_of(p), wq, static_mask, o, st);
+  if (rc != SQ_OK) return rc;
+  return sq::launch_weight_prepack_lo(p->N, p->K, p->bank, p->topk, wq, static_mask,
+                                      o + static_cast<size_t>(p->N) * (k_hi_of(p) / 2), st);
 }
 
 size_t sq_calibrate_workspace_bytes(const sq_params* p, int64_t T) {
@@ -188,8 +200,10 @@ int sq_encode(const sq_params* p, const uint16_t* x_bf16, int64_t ldx, const uin
   if (!aligned16(x_bf16) || (ldx % 8)) return SQ_ERR_ALIGN;
   if (p->mode == SQ_STATIC) {
     if (!static_mask) return SQ_ERR_UNSUPPORTED;
-    if (!out || !out->d_lo || !out->hi_val || !out->scale_lo || !out->scale_hi) return SQ_ERR_NULL;
-    if (!aligned16(out->d_lo) || !aligned16(out->hi_val) || !aligned16(static_mask)) return SQ_ERR_ALIGN;
+    if (!out || (!out->d_lo && !out->lo_compact) || !out->hi_val || !out->scale_lo || !out->scale_hi) return SQ_ERR_NULL;
+    if (!aligned16(out->d_lo) || !aligned16(out->hi_val) || !aligned16(static_mask) || !aligned16(out->lo_compact))
+      return SQ_ERR_ALIGN;
+    if (out->lo_compact && !sq::encode_static_gather_supports(*p)) return SQ_ERR_UNSUPPORTED;
     if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
     return sq::launch_encode_static(*p, x_bf16, ldx, static_mask, *out, static_cast<hipStream_t>(stream));
   }
@@ -220,7 +234,9 @@ int sq_gemm(const sq_params* p, const sq_act* a, const sq_weight* w, void* y, in
   g.N = p->N;
   g.K = p->K;
   g.a_lo = a->d_lo;
+  g.K_lo = p->K;
   g.wq = w->wq;
+  g.w_lo = w->wq;
   g.s_lo = a->scale_lo;
   g.s_hi = a->scale_hi;
   g.s_w = w->scale;
@@ -253,6 +269,11 @@ int sq_gemm(const sq_params* p, const sq_act* a, const sq_weight* w, void* y, in
     g.a_hi_compact = a->hi_val;
     g.lda_hi_compact = g.K_hi;
     g.w_hi = static_cast<const uint8_t*>(w->prepacked);
+    if (a->lo_compact) {  // both operands reordered by the mask: the low product skips the high channels
+      g.a_lo = a->lo_compact;
+      g.K_lo = p->K - g.K_hi;
+      g.w_lo = g.w_hi + static_cast<size_t>(p->N) * (g.K_hi / 2);
+    }
   }
   return sq::launch_gemm(g, st);
 }
@@ -270,8 +291,14 @@ int sq_linear(const sq_params* p, const uint16_t* x_bf16, int64_t ldx, const uin
   const ActLayout l = act_layout(p);
   char* ws = static_cast<char*>(workspace);
   sq_act a;
-  a.d_lo = reinterpret_cast<uint8_t*>(ws);
-  ws += align_up(l.d_lo, 256);
+  memset(&a, 0, sizeof a);
+  if (p->mode == SQ_STATIC && sq::encode_static_gather_supports(*p)) {
+    a.lo_compact = reinterpret_cast<uint8_t*>(ws);
+    ws += align_up(lo_compact_bytes(p), 256);
+  } else {
+    a.d_lo = reinterpret_cast<uint8_t*>(ws);
+    ws += align_up(l.d_lo, 256);
+  }
   a.hi_val = reinterpret_cast<int8_t*>(ws);
   ws += align_up(l.hi_val, 256);
   a.scale_lo = reinterpret_cast<float*>(ws);

@@ -27,6 +27,15 @@ bool encode_stream_supports(const sq_params& p);
 int init_encode_stream_kernels();
 int launch_encode_stream(const sq_params& p, const uint16_t* x, int64_t ldx, const sq_act& out, int8_t* image, bool tied,
                          float q_hi, float q_lo, hipStream_t st);
+// Row-staged static encoder (sq_encode_static.hip): shapes it takes, one-time initialisation, launcher.
+bool encode_static_gather_supports(const sq_params& p);
+int init_encode_static_kernels();
+int launch_encode_static_gather(const sq_params& p, const uint16_t* x, int64_t ldx, const uint32_t* mask,
+                                const sq_act& out, hipStream_t st);
+// Static mode: the low channels' weight columns made contiguous; number of malformed banks of a mask -> *bad.
+int launch_weight_prepack_lo(int N, int K, int bank, int topk, const uint8_t* wq, const uint32_t* mask, uint8_t* out,
+                             hipStream_t st);
+int launch_mask_check(int K, int bank, int topk, const uint32_t* mask, int32_t* bad, hipStream_t st);
 // X -> SQ-format, static rule (channel mask shared by all tokens).
 int launch_encode_static(const sq_params& p, const uint16_t* x, int64_t ldx, const uint32_t* mask, const sq_act& out,
                          hipStream_t st);
@@ -44,9 +53,11 @@ int launch_calibrate_static(const sq_params& p, const uint16_t* x, int64_t ldx, 
                             hipStream_t st);
 
 struct GemmArgs {
-  int M, N, K;          // K of the low / full pass
+  int M, N, K;          // K of the layer
+  int K_lo;             // channels of the low pass: K, or K - K_hi when both operands are the reordered ones
   int K_hi;             // channels of the compact high pass (static / dense-W4A8), multiple of 32
-  const uint8_t* a_lo;  // [M, K/2] packed INT4 (nullptr: no low pass)
+  const uint8_t* a_lo;  // [M, K_lo/2] packed INT4 (nullptr: no low pass)
+  const uint8_t* w_lo;  // [N, K_lo/2] weights of the low pass (wq, or the reordered low columns)
   const int8_t* a_hi_dense;  // dynamic: [M, K] zero-padded INT8 in consumer order (nullptr otherwise)
   const int8_t* a_hi_compact;  // static: [M, K_hi] INT8 natural order (nullptr otherwise)
   int64_t lda_hi_compact;      // row stride of a_hi_compact in bytes

@@ -298,6 +298,56 @@ __global__ __launch_bounds__(256) void expand_hi_kernel(const int8_t* __restrict
   dst[1] = my[1];
 }
 
+// Static mode, low part of the reordered weights (Algorithm 2, last step): the columns of the low channels,
+// ascending channel order, made contiguous: out [N, K_lo/2], plain nibble order (code 2i in the low nibble of
+// byte i) -- the order of sq_act::lo_compact.
+__global__ __launch_bounds__(256) void weight_prepack_lo_kernel(int N, int K, int B, int KT,
+                                                                const uint8_t* __restrict__ wq,
+                                                                const uint32_t* __restrict__ mask,
+                                                                uint8_t* __restrict__ out) {
+  const int nlo = B - KT;
+  const int bytes_per_row = (K / B) * nlo / 2;
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (idx >= static_cast<int64_t>(N) * bytes_per_row) return;
+  const int64_t n = idx / bytes_per_row;
+  const int byte = static_cast<int>(idx - n * bytes_per_row);
+  uint32_t res = 0;
+  for (int h = 0; h < 2; ++h) {
+    const int t = 2 * byte + h;  // compact low position
+    const int bank = t / nlo;
+    int r = t % nlo;
+    int ch = -1;
+    for (int i = 0; i < B; ++i) {
+      const int cc = bank * B + i;
+      if (!((mask[cc >> 5] >> (cc & 31)) & 1u)) {
+        if (r == 0) { ch = cc; break; }
+        --r;
+      }
+    }
+    uint32_t code = 0;
+    if (ch >= 0) code = (wq[n * (K / 2) + (ch >> 1)] >> ((ch & 1) * 4)) & 0xFu;
+    res |= code << (4 * h);
+  }
+  out[idx] = static_cast<uint8_t>(res);
+}
+
+// Number of banks of a channel mask that do not hold exactly KT bits -> *bad (one workgroup).
+__global__ __launch_bounds__(256) void mask_check_kernel(int G, int B, int KT, const uint32_t* __restrict__ mask,
+                                                         int32_t* __restrict__ bad) {
+  __shared__ int total;
+  if (threadIdx.x == 0) total = 0;
+  __syncthreads();
+  int mine = 0;
+  for (int g = threadIdx.x; g < G; g += 256) {
+    int c = 0;
+    for (int w = 0; w < B / 32; ++w) c += __popc(mask[g * (B / 32) + w]);
+    mine += c != KT;
+  }
+  if (mine) atomicAdd(&total, mine);
+  __syncthreads();
+  if (threadIdx.x == 0) *bad = total;
+}
+
 // Static mode: compact copy of the high channels' weight columns.  Output row n holds k_hi_padded
 // codes (zero beyond (K/B)*KT); byte j of every group of 8 codes (4 bytes) carries code j in its low and
 // code j+4 in its high nibble, so that the GEMM kernel's nibble widening yields the codes in natural order.
@@ -397,7 +447,8 @@ int init_encode_kernels() {
   SQ_CASE(128, 8) SQ_CASE(128, 16) SQ_CASE(128, 32)
 #undef SQ_CASE
   if (e != hipSuccess) return SQ_ERR_LAUNCH;
-  return init_encode_stream_kernels();
+  const int rc = init_encode_stream_kernels();
+  return rc != SQ_OK ? rc : init_encode_static_kernels();
 }
 
 int launch_encode_dynamic(const sq_params& p, const uint16_t* x, int64_t ldx, const sq_act& out, hipStream_t st) {
@@ -415,6 +466,9 @@ int launch_encode_dynamic(const sq_params& p, const uint16_t* x, int64_t ldx, co
 
 int launch_encode_static(const sq_params& p, const uint16_t* x, int64_t ldx, const uint32_t* mask, const sq_act& out,
                          hipStream_t st) {
+  // rows that fit in LDS take the row-staged kernel (which can also write the reordered low part); the kernel
+  // below covers the longer ones (dense low part only: the caller has checked that no lo_compact is asked for)
+  if (encode_static_gather_supports(p)) return launch_encode_static_gather(p, x, ldx, mask, out, st);
   if (p.bank == 32) return launch_stat<32>(p, x, ldx, mask, out, st);
   if (p.bank == 64) return launch_stat<64>(p, x, ldx, mask, out, st);
   if (p.bank == 128) return launch_stat<128>(p, x, ldx, mask, out, st);
@@ -435,6 +489,20 @@ int launch_weight_prepack(int N, int K, int bank, int topk, int k_hi_padded, con
   const int64_t blocks = (total + 255) / 256;
   hipLaunchKernelGGL(weight_prepack_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, N, K, bank, topk,
                      k_hi_padded, wq, mask, out);
+  return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+int launch_weight_prepack_lo(int N, int K, int bank, int topk, const uint8_t* wq, const uint32_t* mask, uint8_t* out,
+                             hipStream_t st) {
+  const int64_t total = static_cast<int64_t>(N) * ((K / bank) * (bank - topk) / 2);
+  const int64_t blocks = (total + 255) / 256;
+  hipLaunchKernelGGL(weight_prepack_lo_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, N, K, bank, topk,
+                     wq, mask, out);
+  return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+int launch_mask_check(int K, int bank, int topk, const uint32_t* mask, int32_t* bad, hipStream_t st) {
+  hipLaunchKernelGGL(mask_check_kernel, dim3(1), dim3(256), 0, st, K / bank, bank, topk, mask, bad);
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 

@@ -493,7 +493,7 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmArgs g) {
     p1.init(g.a_lo, g.K / 2, g.a_hi_dense, g.K, g.wq, g.K / 2, g.K, m0, n0, g.M, g.N);
     k_loop_start<T, true, HI1>(p1, lds);
   } else if constexpr (MODE == 1) {
-    p1.init(g.a_lo, g.K / 2, nullptr, 0, g.wq, g.K / 2, g.K, m0, n0, g.M, g.N);
+    p1.init(g.a_lo, g.K_lo / 2, nullptr, 0, g.w_lo, g.K_lo / 2, g.K_lo, m0, n0, g.M, g.N);
     k_loop_start<T, true, HI1>(p1, lds);
   } else {
     p2.init(nullptr, 0, g.a_hi_compact, g.lda_hi_compact, g.w_hi, g.K_hi / 2, g.K_hi, m0, n0, g.M, g.N);

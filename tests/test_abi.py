@@ -51,7 +51,10 @@ def test_sizes(L):
     assert sq.sq_linear_workspace_bytes(p) >= nb.total + 4096 * 4096  # an sq_act plus its hi_dense image
     assert sq.sq_weight_prepack_bytes(p) == 0
     ps = sq.params(4096, 11008, 4096, 64, 8, mode=sq.SQ_STATIC)
-    assert sq.sq_weight_prepack_bytes(ps) == 4096 * (11008 // 64 * 8) // 2
+    assert sq.sq_weight_prepack_bytes(ps) == 4096 * 11008 // 2          # every column once: high ones, then low ones
+    assert sq.sq_lo_compact_bytes(ps) == 4096 * (11008 - 11008 // 64 * 8) // 2 and sq.sq_lo_compact_bytes(p) == 0
+    # static sq_linear keeps only what sq_gemm multiplies: the reordered low part, the high codes, the scales
+    assert sq.sq_linear_workspace_bytes(ps) < 4096 * (11008 // 2) + 4096 * (11008 // 8)  # less than dense low + high
     assert sq.sq_gemm_workspace_bytes(ps) == 16
     assert sq.sq_act_bytes(ps).mask == 11008 // 32 * 4
 
@@ -156,10 +159,12 @@ def test_prepack_checks_the_mask_on_the_host(L):
     good[0::2] = 0xFF  # 8 bits in every bank of 64
     bad = good.copy()
     bad[2] = 0x7F
-    assert L.sq_weight_prepack(ctypes.byref(ps), FAKE, bad.ctypes.data, FAKE, FAKE, None) == -6
+    assert L.sq_weight_prepack(ctypes.byref(ps), FAKE, bad.ctypes.data, FAKE, FAKE, None, None) == -6
     pd = sq.params(16, 512, 512, 64, 8, mode=0)
-    assert L.sq_weight_prepack(ctypes.byref(pd), FAKE, good.ctypes.data, FAKE, FAKE, None) == -3
-    assert L.sq_weight_prepack(ctypes.byref(ps), None, good.ctypes.data, FAKE, FAKE, None) == -1
+    assert L.sq_weight_prepack(ctypes.byref(pd), FAKE, good.ctypes.data, FAKE, FAKE, None, None) == -3
+    assert L.sq_weight_prepack(ctypes.byref(ps), None, good.ctypes.data, FAKE, FAKE, None, None) == -1
+    assert L.sq_weight_prepack(ctypes.byref(ps), FAKE, None, None, FAKE, None, None) == -1   # the device mask is required
+    assert L.sq_weight_prepack(ctypes.byref(ps), FAKE, None, FAKE + 4, FAKE, None, None) == -4
 
 
 def test_binding_refuses_host_tensors():

@@ -229,6 +229,66 @@ def test_gemm_static(M, K, N, bank, topk):
     assert_outputs_close(y, prod, enc, sw)
 
 
+def compact_low(enc):
+    """The oracle's low codes of the low channels only, ascending channel order, two per byte."""
+    flags = ((enc.mask[:, None] >> np.arange(32, dtype=np.uint32)[None, :]) & 1).reshape(-1).astype(bool)
+    d = workloads.unpack_int4(enc.d_lo)[:, ~flags]
+    return pack_int4(d)
+
+
+@pytest.mark.parametrize("M,K,N,bank,topk", [(16, 512, 512, 64, 8), (150, 1024, 200, 32, 4), (40, 11008, 64, 64, 8),
+                                             (70, 2048, 130, 128, 16), (33, 1024, 96, 64, 2)])
+def test_static_reordered_operands(M, K, N, bank, topk):
+    """Static mode with both operands reordered by the mask (Algorithm 2's last step; Section 3.3): sq_encode
+    writes the low codes of the low channels only, sq_weight_prepack -- from the device copy of the mask alone --
+    makes the matching weight columns contiguous, and the low product runs over K - K_hi channels.  The
+    accumulators must be the oracle's (disjoint supports: skipping the zeros changes nothing)."""
+    _say(f"static reordered M={M} K={K} N={N} bank={bank} topk={topk}")
+    bits, wq, sw = random_case(2500 + M + K + N, M, K, N)
+    mask = make_static_mask(K, bank, topk, seed=K + 5)
+    enc = oracle.encode(bits, bank, topk, static_mask=mask)
+    prod = oracle.gemm(enc, wq, sw)
+    p = sq.params(M, K, N, bank, topk, mode=sq.SQ_STATIC, out_dtype=sq.SQ_OUT_F32)
+    wqd, md = dev(wq), dev(mask)
+    pre = torch.empty(sq.sq_weight_prepack_bytes(p), dtype=torch.uint8, device="cuda")
+    bad = torch.full((1,), 77, dtype=torch.int32, device="cuda")
+    sq.sq_weight_prepack(p, wqd, None, md, pre, bad_banks=bad)   # no host copy of the mask
+    # the reordered weights: high columns, then low columns
+    flags = ((mask[:, None] >> np.arange(32, dtype=np.uint32)[None, :]) & 1).reshape(-1).astype(bool)
+    wfull = workloads.unpack_int4(wq)
+    K_hi = K // bank * topk
+    pre_h = pre.cpu().numpy()
+    assert int(bad.item()) == 0
+    assert np.array_equal(pre_h[N * K_hi // 2:].reshape(N, (K - K_hi) // 2), pack_int4(wfull[:, ~flags]))
+    # encoder: reordered low part next to the format's arrays
+    act = GuardedAct(p, static_mask=md)
+    lo = Guarded(sq.sq_lo_compact_bytes(p), torch.uint8)
+    act.lo_compact = lo.t
+    sq.sq_encode(p, dev(bits), act, static_mask=md)
+    torch.cuda.synchronize()
+    act.check()
+    lo.check()
+    assert_encoding_equal(act, enc)
+    assert np.array_equal(lo.host(np.uint8).reshape(M, -1), compact_low(enc))
+    # product on the reordered operands
+    y = Guarded(M * N * 4, torch.float32)
+    alo, ahi = Guarded(M * N * 4, torch.int32), Guarded(M * N * 4, torch.int32)
+    sq.sq_gemm(p, act, sq.weight(wqd, dev(sw), pre), y.t, None, acc_lo_dbg=alo.t, acc_hi_dbg=ahi.t)
+    torch.cuda.synchronize()
+    for g in (y, alo, ahi):
+        g.check()
+    assert np.array_equal(alo.host(np.int32).reshape(M, N), prod.acc_lo), "acc_lo"
+    assert np.array_equal(ahi.host(np.int32).reshape(M, N), prod.acc_hi), "acc_hi"
+    assert np.array_equal(y.host(np.uint32).reshape(M, N), prod.y32.view(np.uint32))
+    # a malformed device mask is reported through bad_banks
+    broken = mask.copy()
+    broken[0] ^= np.uint32(1 << 5)
+    broken[K // 32 - 1] ^= np.uint32(1 << 7)
+    sq.sq_weight_prepack(p, wqd, None, dev(broken), pre, bad_banks=bad)
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 2
+
+
 @pytest.mark.parametrize("mode", ["dynamic", "static"])
 def test_linear_end_to_end(mode):
     _say(f"linear {mode}")
