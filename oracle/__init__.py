@@ -202,3 +202,44 @@ def encode_tied(x_bits: np.ndarray, bank: int, topk: int):
 def gemm_tied(enc, wq_packed: np.ndarray, w_scale: np.ndarray):
     """The single integer product of the tied-scale layer and its dequantised output."""
     return _tied().gemm_tied(enc, wq_packed, w_scale)
+
+
+# ---- other precision pairs and the bit-packed storage (oracle/pairs.py, plain numpy) ----
+_pairs_mod = None
+
+
+def _pairs():
+    """oracle.pairs, or -- only for the test that plants mistakes in it -- the copy named by SQ_ORACLE_PAIRS_SRC."""
+    global _pairs_mod
+    if _pairs_mod is None:
+        import importlib
+        import importlib.util
+
+        override = os.environ.get("SQ_ORACLE_PAIRS_SRC")
+        if override:
+            spec = importlib.util.spec_from_file_location(__name__ + ".pairs_variant", override)
+            mod = importlib.util.module_from_spec(spec)
+            mod.__package__ = __name__
+            spec.loader.exec_module(mod)
+            _pairs_mod = mod
+        else:
+            _pairs_mod = importlib.import_module(__name__ + ".pairs")
+    return _pairs_mod
+
+
+def encode_pair(x_bits, bank, topk, h_high, h_low, static_mask=None):
+    """SQ-format with the precision pair (h_high/h_low) of Section 4.1 / Table 3; see oracle/pairs.py."""
+    return _pairs().encode_pair(x_bits, bank, topk, h_high, h_low, static_mask)
+
+
+def pack_storage(enc, h_high, h_low):
+    """The encoding as a bit stream of exactly K*y/8 bytes per row, y = (1-s) h_high + s h_low (Section 4.1)."""
+    return _pairs().pack_storage(enc, h_high, h_low)
+
+
+def unpack_storage(packed, mask, K, bank, topk, h_high, h_low, s_lo, s_hi, static=False):
+    return _pairs().unpack_storage(packed, mask, K, bank, topk, h_high, h_low, s_lo, s_hi, static)
+
+
+def storage_row_bytes(K, bank, topk, h_high, h_low):
+    return _pairs().storage_row_bytes(K, bank, topk, h_high, h_low)

@@ -176,7 +176,7 @@ def test_equivalent_bits_match_paper_table():
     import os
     path = os.path.join(os.path.dirname(__file__), "golden", "equivalent_bits_table3.txt")
     rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
-    assert len(rows) == 7
+    assert len(rows) == 14
     for hh, hl, s, y in rows:
         assert oracle.equivalent_bits(float(hh), float(hl), float(s)) == pytest.approx(float(y), abs=1e-12)
     # the layout stored here keeps the low part dense and adds an explicit mask bit
