@@ -75,6 +75,12 @@ typedef struct {
                         >= bank/16 (the sparsities 1/2 ... 15/16 of Section 4.1); static mode: (K/bank)*topk % 32 == 0 */
   int32_t mode;      /* SQ_DYNAMIC, SQ_STATIC or SQ_DYNAMIC_TIED */
   int32_t out_dtype; /* SQ_OUT_F32 or SQ_OUT_BF16 */
+  int32_t h_high;    /* bits of the high-precision codes: 8 or 4; 0 = 8 */
+  int32_t h_low;     /* bits of the low-precision codes: 4, 3 or 2; 0 = 4.  Supported pairs (Section 4.1, Table 3):
+                        8/4, 8/3, 8/2, 4/2.  The codes are symmetric, |code| <= 2^(bits-1) - 1, and travel in the
+                        same containers whatever the pair (INT8 bytes in hi_val, 4-bit nibbles in d_lo), so the
+                        products are the same kernels; sq_pack_storage writes them at their true widths.
+                        SQ_DYNAMIC_TIED takes 8/4 only. */
 } sq_params;
 
 /* An activation matrix in SQ-format: ([X_quant], [S_quant], [m]) of Eq. (1). */
@@ -109,6 +115,21 @@ typedef struct {
   const float *scale;     /* [N] */
   const void *prepacked;  /* static mode: output of sq_weight_prepack (required); dynamic modes: ignored, may be NULL */
 } sq_weight;
+
+/*
+ * The format at its equivalent bit width (Section 4.1: y = (1-s)*h_high + s*h_low bits per element): per token
+ * row a bit stream of K*y/8 bytes = the high codes of the high channels at h_high bits each, then the low codes
+ * of the LOW channels only at h_low bits each, ascending channel order; code t of a section occupies its bits
+ * [t*h, (t+1)*h), bit i of a section is bit i%8 of its byte i/8, two's complement.  The mask and the scales of
+ * the sq_act are stored beside it, unchanged.
+ *   sq_storage_row_bytes: K*y/8 (0 for invalid parameters)
+ *   sq_pack_storage:   a (d_lo, hi_val, mask as in sq_gemm)  ->  packed device [M, sq_storage_row_bytes(p)]
+ *   sq_unpack_storage: packed, a->mask  ->  a->d_lo, a->hi_val   (the exact inverse)
+ * Storage conversions, not part of the layer's hot path; they only enqueue work on `stream`.
+ */
+size_t sq_storage_row_bytes(const sq_params *p);
+int sq_pack_storage(const sq_params *p, const sq_act *a, uint8_t *packed, void *stream);
+int sq_unpack_storage(const sq_params *p, const uint8_t *packed, const sq_act *a, void *stream);
 
 /* Per-device initialisation for the current device (idempotent, thread-safe): raises the kernels' dynamic-LDS
  * limits.  Every launching entry point does this on its first call on a device; call it explicitly before a

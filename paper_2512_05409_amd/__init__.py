@@ -23,6 +23,7 @@ EXPORTS = (
     "sq_weight_prepack", "sq_encode", "sq_gemm", "sq_linear", "sq_dense_w4a8_prepack", "sq_dense_w4a8_gemm",
     "sq_calibrate_workspace_bytes", "sq_calibrate_static", "sq_probe_mfma_i8", "sq_probe_stream", "sq_status_string", "sq_version",
     "sq_init", "sq_gemm_variant", "sq_linear_noalloc", "sq_lo_compact_bytes",
+    "sq_storage_row_bytes", "sq_pack_storage", "sq_unpack_storage",
 )
 SQ_NOALLOC_SCRATCH_BYTES = 8 << 20
 
@@ -35,7 +36,8 @@ class SqError(RuntimeError):
 
 class sq_params(ctypes.Structure):
     _fields_ = [("M", ctypes.c_int32), ("K", ctypes.c_int32), ("N", ctypes.c_int32), ("bank", ctypes.c_int32),
-                ("topk", ctypes.c_int32), ("mode", ctypes.c_int32), ("out_dtype", ctypes.c_int32)]
+                ("topk", ctypes.c_int32), ("mode", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+                ("h_high", ctypes.c_int32), ("h_low", ctypes.c_int32)]
 
 
 class sq_act(ctypes.Structure):
@@ -84,6 +86,12 @@ def lib() -> ctypes.CDLL:
         L.sq_status_string.argtypes = [ctypes.c_int]
         L.sq_status_string.restype = ctypes.c_char_p
         L.sq_version.restype = ctypes.c_char_p
+        L.sq_storage_row_bytes.argtypes = [P(sq_params)]
+        L.sq_storage_row_bytes.restype = sz
+        L.sq_pack_storage.argtypes = [P(sq_params), P(sq_act), vp, vp]
+        L.sq_unpack_storage.argtypes = [P(sq_params), vp, P(sq_act), vp]
+        L.sq_pack_storage.restype = ctypes.c_int
+        L.sq_unpack_storage.restype = ctypes.c_int
         L.sq_init.argtypes = []
         L.sq_init.restype = ctypes.c_int
         L.sq_gemm_variant.argtypes = [P(sq_params)]
@@ -109,8 +117,8 @@ def sq_gemm_variant(p: "sq_params") -> str:
 
 
 def params(M: int, K: int, N: int, bank: int = 64, topk: int = 8, mode: int = SQ_DYNAMIC,
-           out_dtype: int = SQ_OUT_BF16) -> sq_params:
-    return sq_params(int(M), int(K), int(N), int(bank), int(topk), int(mode), int(out_dtype))
+           out_dtype: int = SQ_OUT_BF16, h_high: int = 0, h_low: int = 0) -> sq_params:
+    return sq_params(int(M), int(K), int(N), int(bank), int(topk), int(mode), int(out_dtype), int(h_high), int(h_low))
 
 
 def _check(rc: int, where: str) -> None:
@@ -238,6 +246,20 @@ def sq_linear_noalloc(p: sq_params, x_bf16, w: sq_weight, y, static_mask=None, l
     _check(lib().sq_linear_noalloc(ctypes.byref(p), _ptr(x_bf16), p.K if ldx is None else ldx, _ptr(static_mask),
                                    ctypes.byref(w), _ptr(y), p.N if ldy is None else ldy, _stream(stream)),
            "sq_linear_noalloc")
+
+
+def sq_storage_row_bytes(p: sq_params) -> int:
+    return int(lib().sq_storage_row_bytes(ctypes.byref(p)))
+
+
+def sq_pack_storage(p: sq_params, a: Act, packed, stream=None) -> None:
+    ac = a.c()
+    _check(lib().sq_pack_storage(ctypes.byref(p), ctypes.byref(ac), _ptr(packed), _stream(stream)), "sq_pack_storage")
+
+
+def sq_unpack_storage(p: sq_params, packed, a: Act, stream=None) -> None:
+    ac = a.c()
+    _check(lib().sq_unpack_storage(ctypes.byref(p), _ptr(packed), ctypes.byref(ac), _stream(stream)), "sq_unpack_storage")
 
 
 def sq_dense_w4a8_prepack(p: sq_params, wq, out, stream=None) -> None:

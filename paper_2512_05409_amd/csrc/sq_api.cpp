@@ -47,6 +47,12 @@ int check_params(const sq_params* p) {
   if (p->mode != SQ_STATIC && p->topk * 16 < p->bank) return SQ_ERR_UNSUPPORTED;  // s in {1/2,3/4,7/8,15/16}
   if (p->mode == SQ_DYNAMIC_TIED && !sq::encode_stream_supports(*p)) return SQ_ERR_UNSUPPORTED;
   if (p->mode == SQ_STATIC && ((p->K / p->bank) * p->topk) % 32) return SQ_ERR_UNSUPPORTED;
+  {  // precision pair (Section 4.1): 0/0 = 8/4, or one of 8/4, 8/3, 8/2, 4/2
+    const int hh = p->h_high ? p->h_high : 8, hl = p->h_low ? p->h_low : 4;
+    const bool ok = (hh == 8 && (hl == 4 || hl == 3 || hl == 2)) || (hh == 4 && hl == 2);
+    if (!ok) return SQ_ERR_UNSUPPORTED;
+    if (p->mode == SQ_DYNAMIC_TIED && !(hh == 8 && hl == 4)) return SQ_ERR_UNSUPPORTED;
+  }
   return SQ_OK;
 }
 
@@ -211,7 +217,7 @@ int sq_encode(const sq_params* p, const uint16_t* x_bf16, int64_t ldx, const uin
   if (rc != SQ_OK) return rc;
   if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
   if (p->mode == SQ_DYNAMIC_TIED)
-    return sq::launch_encode_stream(*p, x_bf16, ldx, *out, out->hi_dense, true, 127.0f, 7.0f, static_cast<hipStream_t>(stream));
+    return sq::launch_encode_stream(*p, x_bf16, ldx, *out, out->hi_dense, true, 127.0f, 7.0f, static_cast<hipStream_t>(stream));  // (8/4) only
   return sq::launch_encode_dynamic(*p, x_bf16, ldx, *out, static_cast<hipStream_t>(stream));
 }
 
@@ -317,6 +323,29 @@ int sq_linear(const sq_params* p, const uint16_t* x_bf16, int64_t ldx, const uin
   rc = sq_encode(p, x_bf16, ldx, static_mask, &a, stream);
   if (rc != SQ_OK) return rc;
   return sq_gemm(p, &a, w, y, ldy, nullptr, nullptr, nullptr, 0, stream);
+}
+
+size_t sq_storage_row_bytes(const sq_params* p) {
+  if (check_params(p) != SQ_OK) return 0;
+  const int hh = p->h_high ? p->h_high : 8, hl = p->h_low ? p->h_low : 4;
+  return static_cast<size_t>(k_hi_of(p)) * hh / 8 + static_cast<size_t>(p->K - k_hi_of(p)) * hl / 8;
+}
+
+static int storage_call(const sq_params* p, const sq_act* a, uint8_t* packed, bool pack, void* stream) {
+  int rc = check_params(p);
+  if (rc != SQ_OK) return rc;
+  if (!a || !a->d_lo || !a->hi_val || !a->mask || !packed) return SQ_ERR_NULL;
+  if (!aligned16(a->d_lo) || !aligned16(a->hi_val) || !aligned16(a->mask)) return SQ_ERR_ALIGN;
+  if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
+  return sq::launch_storage(*p, *a, packed, pack, static_cast<hipStream_t>(stream));
+}
+
+int sq_pack_storage(const sq_params* p, const sq_act* a, uint8_t* packed, void* stream) {
+  return storage_call(p, a, packed, true, stream);
+}
+
+int sq_unpack_storage(const sq_params* p, const uint8_t* packed, const sq_act* a, void* stream) {
+  return storage_call(p, a, const_cast<uint8_t*>(packed), false, stream);
 }
 
 int sq_dense_w4a8_prepack(const sq_params* p, const uint8_t* wq, void* out, void* stream) {

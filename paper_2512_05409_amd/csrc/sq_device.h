@@ -7,6 +7,11 @@
 
 namespace sq {
 
+// Largest code magnitude of a symmetric integer format of `bits` bits (0: the default width), Section 3.2.1.
+inline float code_max(int bits, int default_bits) {
+  return static_cast<float>((1 << ((bits ? bits : default_bits) - 1)) - 1);
+}
+
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
@@ -51,6 +56,9 @@ void calibrate_chunks(int64_t T, int N, int* chunks_a, int* rows_a, int* chunks_
 int launch_calibrate_static(const sq_params& p, const uint16_t* x, int64_t ldx, int64_t T, const uint8_t* wq,
                             const float* s_w, uint32_t* mask, double* importance, double* partial_a, double* partial_w,
                             hipStream_t st);
+
+// Pack / unpack the bit-packed storage stream (sq_storage.hip).
+int launch_storage(const sq_params& p, const sq_act& act, uint8_t* packed, bool pack, hipStream_t st);
 
 struct GemmArgs {
   int M, N, K;          // K of the layer

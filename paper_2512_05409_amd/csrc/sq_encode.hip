@@ -57,7 +57,7 @@ __global__ __launch_bounds__(MAXT) void encode_dynamic_kernel(const uint16_t* __
                                                               int G, int R, uint8_t* __restrict__ d_lo,
                                                               int8_t* __restrict__ hi_val, uint32_t* __restrict__ mask,
                                                               float* __restrict__ s_lo, float* __restrict__ s_hi,
-                                                              int8_t* __restrict__ hi_dense) {
+                                                              int8_t* __restrict__ hi_dense, float q_hi, float q_lo) {
   extern __shared__ __attribute__((aligned(16))) char dense_stage[];  // blockDim * B bytes when hi_dense is set
   static_assert(B % 32 == 0 && KT >= 1 && KT <= 32 && (KT & (KT - 1)) == 0 && B % KT == 0 && B / KT >= 2, "shape");
   __shared__ uint32_t amax_sh[64];
@@ -114,11 +114,11 @@ __global__ __launch_bounds__(MAXT) void encode_dynamic_kernel(const uint16_t* __
 
   const uint32_t ah = amax_sh[2 * c.r_local], al = amax_sh[2 * c.r_local + 1];
   const float amax_hi = __uint_as_float(ah << 16), amax_lo = __uint_as_float(al << 16);
-  const float inv_hi = ah ? 127.0f / amax_hi : 0.0f;
-  const float inv_lo = al ? 7.0f / amax_lo : 0.0f;
+  const float inv_hi = ah ? q_hi / amax_hi : 0.0f;
+  const float inv_lo = al ? q_lo / amax_lo : 0.0f;
   if (c.g == 0) {
-    s_hi[c.row] = ah ? amax_hi / 127.0f : 1.0f;
-    s_lo[c.row] = al ? amax_lo / 7.0f : 1.0f;
+    s_hi[c.row] = ah ? amax_hi / q_hi : 1.0f;
+    s_lo[c.row] = al ? amax_lo / q_lo : 1.0f;
   }
 
   // ---- high part: quantise the k selected values, order them by channel, emit codes and mask ----
@@ -184,7 +184,8 @@ template <int B, int MAXT>
 __global__ __launch_bounds__(MAXT) void encode_static_kernel(const uint16_t* __restrict__ x, int64_t ldx, int M, int K,
                                                              int G, int R, int kt, const uint32_t* __restrict__ cmask,
                                                              uint8_t* __restrict__ d_lo, int8_t* __restrict__ hi_val,
-                                                             float* __restrict__ s_lo, float* __restrict__ s_hi) {
+                                                             float* __restrict__ s_lo, float* __restrict__ s_hi,
+                                                             float q_hi, float q_lo) {
   __shared__ uint32_t amax_sh[64];
   __shared__ int8_t stage[MAXT * 32];  // per lane: up to 32 high codes in channel order
   if (threadIdx.x < 64) amax_sh[threadIdx.x] = 0;
@@ -221,11 +222,11 @@ __global__ __launch_bounds__(MAXT) void encode_static_kernel(const uint16_t* __r
 
   const uint32_t ah = amax_sh[2 * c.r_local], al = amax_sh[2 * c.r_local + 1];
   const float amax_hi = __uint_as_float(ah << 16), amax_lo = __uint_as_float(al << 16);
-  const float inv_hi = ah ? 127.0f / amax_hi : 0.0f;
-  const float inv_lo = al ? 7.0f / amax_lo : 0.0f;
+  const float inv_hi = ah ? q_hi / amax_hi : 0.0f;
+  const float inv_lo = al ? q_lo / amax_lo : 0.0f;
   if (c.g == 0) {
-    s_hi[c.row] = ah ? amax_hi / 127.0f : 1.0f;
-    s_lo[c.row] = al ? amax_lo / 7.0f : 1.0f;
+    s_hi[c.row] = ah ? amax_hi / q_hi : 1.0f;
+    s_lo[c.row] = al ? amax_lo / q_lo : 1.0f;
   }
 
   int8_t* my = stage + threadIdx.x * 32;
@@ -392,7 +393,7 @@ int launch_dyn_t(const sq_params& p, const uint16_t* x, int64_t ldx, const sq_ac
   // up to MAXT * B bytes; the limit of every instantiation was raised by init_encode_kernels
   const size_t lds = o.hi_dense ? static_cast<size_t>(threads) * B : 0;
   hipLaunchKernelGGL((encode_dynamic_kernel<B, KT, MAXT>), dim3(blocks), dim3(threads), lds, st, x, ldx, p.M, p.K, G, R,
-                     o.d_lo, o.hi_val, o.mask, o.scale_lo, o.scale_hi, o.hi_dense);
+                     o.d_lo, o.hi_val, o.mask, o.scale_lo, o.scale_hi, o.hi_dense, code_max(p.h_high, 8), code_max(p.h_low, 4));
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
@@ -419,10 +420,10 @@ int launch_stat(const sq_params& p, const uint16_t* x, int64_t ldx, const uint32
   const int blocks = (p.M + R - 1) / R;
   if (threads <= 256) {
     hipLaunchKernelGGL((encode_static_kernel<B, 256>), dim3(blocks), dim3(threads), 0, st, x, ldx, p.M, p.K, G, R,
-                       p.topk, mask, o.d_lo, o.hi_val, o.scale_lo, o.scale_hi);
+                       p.topk, mask, o.d_lo, o.hi_val, o.scale_lo, o.scale_hi, code_max(p.h_high, 8), code_max(p.h_low, 4));
   } else {
     hipLaunchKernelGGL((encode_static_kernel<B, 512>), dim3(blocks), dim3(threads), 0, st, x, ldx, p.M, p.K, G, R,
-                       p.topk, mask, o.d_lo, o.hi_val, o.scale_lo, o.scale_hi);
+                       p.topk, mask, o.d_lo, o.hi_val, o.scale_lo, o.scale_hi, code_max(p.h_high, 8), code_max(p.h_low, 4));
   }
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
@@ -454,7 +455,8 @@ int init_encode_kernels() {
 int launch_encode_dynamic(const sq_params& p, const uint16_t* x, int64_t ldx, const sq_act& out, hipStream_t st) {
   // Rows whose bank count is a power of two up to 64, or 64 / 128 / 256, take the streaming kernel; the
   // kernel below covers every other K / bank <= 512 (checked by the caller).
-  if (encode_stream_supports(p)) return launch_encode_stream(p, x, ldx, out, out.hi_dense, false, 127.0f, 7.0f, st);
+  if (encode_stream_supports(p))
+    return launch_encode_stream(p, x, ldx, out, out.hi_dense, false, code_max(p.h_high, 8), code_max(p.h_low, 4), st);
 #define SQ_CASE(B, KT) \
   if (p.bank == B && p.topk == KT) return launch_dyn<B, KT>(p, x, ldx, out, st);
   SQ_CASE(32, 2) SQ_CASE(32, 4) SQ_CASE(32, 8) SQ_CASE(32, 16)

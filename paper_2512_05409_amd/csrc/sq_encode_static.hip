@@ -42,6 +42,7 @@ struct GatherArgs {
   float* s_lo;
   float* s_hi;
   int row_bytes_padded;   // LDS bytes of the staged row (K * 2 rounded up to 4096)
+  float q_hi, q_lo;       // largest code magnitudes of the two parts (127 and 7 for the 8/4 pair)
 };
 
 // MAXI: output dwords of each kind a thread owns at most (K / 8 / 256 rounded up).
@@ -168,11 +169,11 @@ __global__ __launch_bounds__(NT) void encode_static_gather_kernel(GatherArgs a) 
     __syncthreads();  // barrier C
     const uint32_t ah = amax_sh[par][0], al = amax_sh[par][1];
     const float amax_hi = __uint_as_float(ah << 16), amax_lo = __uint_as_float(al << 16);
-    const float inv_hi = ah ? 127.0f / amax_hi : 0.0f;
-    const float inv_lo = al ? 7.0f / amax_lo : 0.0f;
+    const float inv_hi = ah ? a.q_hi / amax_hi : 0.0f;
+    const float inv_lo = al ? a.q_lo / amax_lo : 0.0f;
     if (tid == 0) {
-      a.s_hi[m] = ah ? amax_hi / 127.0f : 1.0f;
-      a.s_lo[m] = al ? amax_lo / 7.0f : 1.0f;
+      a.s_hi[m] = ah ? amax_hi / a.q_hi : 1.0f;
+      a.s_lo[m] = al ? amax_lo / a.q_lo : 1.0f;
     }
 
     // ---- quantise from the registers: whole output dwords per thread, coalesced stores ----
@@ -243,6 +244,8 @@ int launch_encode_static_gather(const sq_params& p, const uint16_t* x, int64_t l
   a.hi_val = out.hi_val;
   a.s_lo = out.scale_lo;
   a.s_hi = out.scale_hi;
+  a.q_hi = code_max(p.h_high, 8);
+  a.q_lo = code_max(p.h_low, 4);
   a.row_bytes_padded = static_cast<int>((static_cast<size_t>(p.K) * 2 + 4095) / 4096 * 4096);
   const size_t lds = gather_lds_bytes(p.K);
   int dev = 0, cus = 256;
