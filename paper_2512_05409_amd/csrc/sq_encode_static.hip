@@ -27,6 +27,12 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+// max of two pairs of 16-bit magnitudes, both halves in one instruction (v_pk_max_u16)
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b)));
+}
 
 constexpr int NT = 256;
 
@@ -103,34 +109,44 @@ __global__ __launch_bounds__(NT) void encode_static_gather_kernel(GatherArgs a) 
 
     // ---- gather: every thread fetches the source values of the output dwords it owns, packed two bf16 per
     // register, and takes the maxima of their magnitudes on the way ----
+    // (Threads whose dword index is past the end gather the last dword again instead of being masked off:
+    // without branches all the gathers of a thread are in flight together and it waits once.)
     uint32_t vlo[MAXI][4], vhi[MAXI][2], vde[MAXI][4];
     uint32_t mx_hi = 0, mx_lo = 0;  // packed: two 15-bit magnitudes per register
+    const int it_lo = (n_lo + NT - 1) / NT, it_hi = (n_hi + NT - 1) / NT, it_de = (n_dense + NT - 1) / NT;  // uniform
+    {
 #pragma unroll
-    for (int i = 0; i < MAXI; ++i) {
-      const int j = i * NT + tid;
-      if (j < n_lo) {
+      for (int i = 0; i < MAXI; ++i) {
+        if (i >= it_lo) break;
+        const int j = min(i * NT + tid, n_lo - 1);
         const u16x8 idx = *reinterpret_cast<const u16x8*>(src_lo + 8 * j);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const uint32_t x0 = *reinterpret_cast<const uint16_t*>(row + 2 * idx[2 * q]);
           const uint32_t x1 = *reinterpret_cast<const uint16_t*>(row + 2 * idx[2 * q + 1]);
           vlo[i][q] = x0 | (x1 << 16);
-          mx_lo = __builtin_elementwise_max(mx_lo & 0xFFFFu, vlo[i][q] & 0x7FFFu) |
-                  (__builtin_elementwise_max(mx_lo >> 16, (vlo[i][q] >> 16) & 0x7FFFu) << 16);
+          mx_lo = pk_max_u16(mx_lo, vlo[i][q] & 0x7FFF7FFFu);
         }
       }
-      if (j < n_hi) {
-        const u16x4 idx = *reinterpret_cast<const u16x4*>(src_hi + 4 * j);
+    }
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-          const uint32_t x0 = *reinterpret_cast<const uint16_t*>(row + 2 * idx[2 * q]);
-          const uint32_t x1 = *reinterpret_cast<const uint16_t*>(row + 2 * idx[2 * q + 1]);
-          vhi[i][q] = x0 | (x1 << 16);
-          mx_hi = __builtin_elementwise_max(mx_hi & 0xFFFFu, vhi[i][q] & 0x7FFFu) |
-                  (__builtin_elementwise_max(mx_hi >> 16, (vhi[i][q] >> 16) & 0x7FFFu) << 16);
-        }
+    for (int i = 0; i < MAXI; ++i) {
+      if (i >= it_hi) break;
+      const int j = min(i * NT + tid, n_hi - 1);
+      const u16x4 idx = *reinterpret_cast<const u16x4*>(src_hi + 4 * j);
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const uint32_t x0 = *reinterpret_cast<const uint16_t*>(row + 2 * idx[2 * q]);
+        const uint32_t x1 = *reinterpret_cast<const uint16_t*>(row + 2 * idx[2 * q + 1]);
+        vhi[i][q] = x0 | (x1 << 16);
+        mx_hi = pk_max_u16(mx_hi, vhi[i][q] & 0x7FFF7FFFu);
       }
-      if (j < n_dense) {
+    }
+    {
+#pragma unroll
+      for (int i = 0; i < MAXI; ++i) {
+        if (i >= it_de) break;
+        const int j = min(i * NT + tid, n_dense - 1);
         const u32x4 v = *reinterpret_cast<const u32x4*>(row + j * 16);
 #pragma unroll
         for (int q = 0; q < 4; ++q) vde[i][q] = v[q];

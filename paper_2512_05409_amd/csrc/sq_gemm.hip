@@ -35,8 +35,11 @@ constexpr int NT = 256;  // threads per workgroup
 
 // WITH_LO = false: a tile for loops without a packed low operand (the single-product modes), whose stage
 // holds no room for one; that is what lets 256 tokens x 256 channels fit three stages into LDS.
-template <int BM_, int BN_, bool WITH_LO = true>
+// NS: LDS stages of the K loop.  The copy of step kt + NS - 1 is enqueued while step kt is multiplied, so a copy
+// has NS - 2 whole K steps to land before anything waits for it.
+template <int BM_, int BN_, bool WITH_LO = true, int NS_ = 3>
 struct Tile {
+  static constexpr int NS = NS_;
   static constexpr int BM = BM_;              // tokens per workgroup
   static constexpr int BN = BN_;              // output channels per workgroup
   static constexpr int WM = BM / 2;           // tokens per wave (waves are 2 x 2)
@@ -47,7 +50,8 @@ struct Tile {
   static constexpr int A_HI = WITH_LO ? BM * 64 : 0;  // [BM][128 B]  INT8
   static constexpr int B_OFF = A_HI + BM * 128;  // [BN][64 B] packed INT4
   static constexpr int STAGE = B_OFF + BN * 64;
-  static constexpr int LDS_BYTES = 3 * STAGE;
+  static constexpr int LDS_BYTES = NS * STAGE;
+  static_assert(NS >= 3 && LDS_BYTES <= 160 * 1024, "stages must fit in the 160 KB of LDS");
 };
 
 // Byte offset of 16-byte chunk c of a row inside an operand tile.
@@ -242,17 +246,18 @@ __device__ __forceinline__ void interleave() {
 //   barrier (step kt+1 is complete in LDS, step kt's stage may be overwritten)
 //   slice C: multiply w0     | fetch f0 = (step kt+1, channels 0-63), widen f1 slice 1 -> w1
 //   slice D: multiply w1     | widen f0 slice 0 -> w0
-// FILL: 0 = nothing to copy, 1 = the copy of step kt+2 is enqueued, 2 = the same and that step may be
-// partial; NEXT: step kt+1 exists.
-template <typename T, bool LO, bool HI, int FILL, bool NEXT>
+// FILL: 0 = nothing to copy, 1 = the copy of step kt + NS - 1 is enqueued, 2 = the same and that step may be
+// partial; ALLOW: K steps whose copies may still be in flight at the barrier (those after step kt+1);
+// NEXT: step kt+1 exists.
+template <typename T, bool LO, bool HI, int FILL, int ALLOW, bool NEXT>
 __device__ __forceinline__ void k_iteration(const Pipe<T, LO, HI>& pipe, char* lds, int kt, int st_cur, int wm, int wn,
                                             int lane, Frags<T>& f0, Frags<T>& f1, Wide<T>& w0, Wide<T>& w1,
                                             v16i (&acc_lo)[T::TI][T::TJ], v16i (&acc_hi)[T::TI][T::TJ]) {
   constexpr int NL = Pipe<T, LO, HI>::NLOAD;
   constexpr int NM = (LO ? 1 : 0) * T::TI * T::TJ + (HI ? 1 : 0) * T::TI * T::TJ;  // matrix instructions per slice
   constexpr int NR = T::TJ + (LO ? T::TI : 0) + (HI ? 2 * T::TI : 0);               // LDS reads per fragment set
-  const int st_next = st_cur == 2 ? 0 : st_cur + 1;
-  const int st_fill = st_next == 2 ? 0 : st_next + 1;
+  const int st_next = st_cur == T::NS - 1 ? 0 : st_cur + 1;
+  const int st_fill = st_cur == 0 ? T::NS - 1 : st_cur - 1;  // the stage of step kt - 1, read for the last time before the previous barrier
   // slice A
   read_frags<T, LO, HI>(f1, lds + st_cur * T::STAGE, 1, wm, wn, lane);
   widen_slice<T, LO>(w1, f0, 1);
@@ -260,13 +265,13 @@ __device__ __forceinline__ void k_iteration(const Pipe<T, LO, HI>& pipe, char* l
   interleave<NM, 4, 0, 0, NR>();
   __builtin_amdgcn_sched_barrier(0);
   // slice B
-  if (FILL == 1) pipe.template issue<false>(lds + st_fill * T::STAGE, kt + 2);
-  if (FILL == 2) pipe.template issue<true>(lds + st_fill * T::STAGE, kt + 2);
+  if (FILL == 1) pipe.template issue<false>(lds + st_fill * T::STAGE, kt + T::NS - 1);
+  if (FILL == 2) pipe.template issue<true>(lds + st_fill * T::STAGE, kt + T::NS - 1);
   widen_slice<T, LO>(w0, f1, 0);
   mma_slice<T, LO, HI>(w1, f0, 1, acc_lo, acc_hi);
   interleave<NM, 6, 3, FILL ? NL : 0, 0>();
   __builtin_amdgcn_sched_barrier(0);
-  pipeline_barrier<FILL ? NL : 0>();
+  pipeline_barrier<ALLOW * NL>();
   // slice C
   if (NEXT) read_frags<T, LO, HI>(f0, lds + st_next * T::STAGE, 0, wm, wn, lane);
   widen_slice<T, LO>(w1, f1, 1);
@@ -280,47 +285,69 @@ __device__ __forceinline__ void k_iteration(const Pipe<T, LO, HI>& pipe, char* l
   __builtin_amdgcn_sched_barrier(0);
 }
 
-// K loop, three LDS stages: the copy of step kt+2 is enqueued while step kt is multiplied; every wave
-// waits for its own copy of step kt+1 in the middle of iteration kt, the workgroup meets at a barrier,
-// and the matrix pipeline has operands in registers on both sides of it (see k_iteration).  The last
-// two iterations are peeled so that the steady-state body has no branches.
-// Safety: the stage overwritten by the copy of step kt+2 was last read (step kt-1) before the
+// K loop over NS LDS stages: the copy of step kt + NS - 1 is enqueued while step kt is multiplied; every wave
+// waits for its own copy of step kt+1 in the middle of iteration kt (younger copies stay in flight), the
+// workgroup meets at a barrier, and the matrix pipeline has operands in registers on both sides of it (see
+// k_iteration).  The last NS iterations are peeled so that the steady-state body has no branches.
+// Safety: the stage overwritten by the copy of step kt + NS - 1 held step kt-1, last read before the
 // barrier of iteration kt-1, and every wave drains its LDS reads (lgkmcnt 0) before that barrier.
-// k_loop_start enqueues the first two steps; k_loop expects them enqueued (whatever independent work the
+// k_loop_start enqueues the first NS - 1 steps; k_loop expects them enqueued (whatever independent work the
 // caller has goes between the two calls, under the latency of those first copies).
 template <typename T, bool LO, bool HI>
 __device__ __forceinline__ void k_loop_start(const Pipe<T, LO, HI>& pipe, char* lds) {
   pipe.template issue<true>(lds, 0);
-  if (pipe.kext > KS) pipe.template issue<true>(lds + T::STAGE, 1);
+#pragma unroll
+  for (int s0 = 1; s0 < T::NS - 1; ++s0)
+    if (pipe.kext > s0 * KS) pipe.template issue<true>(lds + s0 * T::STAGE, s0);
+}
+
+// The last iterations of a K loop, peeled: with R steps left after the current one, the iteration that still
+// enqueues a copy (R == NS - 1: the last step, which may be partial), then the ones that only drain.
+template <typename T, bool LO, bool HI, int R>
+__device__ __forceinline__ void k_loop_tail(const Pipe<T, LO, HI>& pipe, char* lds, int steps, int& kt, int& st, int wm, int wn,
+                                            int lane, Frags<T>& f0, Frags<T>& f1, Wide<T>& w0, Wide<T>& w1,
+                                            v16i (&acc_lo)[T::TI][T::TJ], v16i (&acc_hi)[T::TI][T::TJ]) {
+  constexpr int D = T::NS - 1;
+  if (steps - 1 - kt == R) {
+    constexpr int FILL = R == D ? 2 : 0;
+    constexpr int ALLOW = R == D ? D - 1 : (R > 0 ? R - 1 : 0);
+    k_iteration<T, LO, HI, FILL, ALLOW, (R > 0)>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
+    st = st == T::NS - 1 ? 0 : st + 1;
+    ++kt;
+  }
+  if constexpr (R > 0) k_loop_tail<T, LO, HI, R - 1>(pipe, lds, steps, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
+}
+
+template <int N, int NL>
+__device__ __forceinline__ void first_barrier(int in_flight) {  // in_flight steps enqueued, step 0 must have landed
+  if constexpr (N > 1) {
+    if (in_flight >= N) {
+      pipeline_barrier<(N - 1) * NL>();
+      return;
+    }
+    first_barrier<N - 1, NL>(in_flight);
+  } else {
+    pipeline_barrier<0>();
+  }
 }
 
 template <typename T, bool LO, bool HI>
 __device__ __forceinline__ void k_loop(const Pipe<T, LO, HI>& pipe, char* lds, int wm, int wn, int lane,
                                        v16i (&acc_lo)[T::TI][T::TJ], v16i (&acc_hi)[T::TI][T::TJ]) {
   constexpr int NL = Pipe<T, LO, HI>::NLOAD;
+  constexpr int D = T::NS - 1;
   const int steps = (pipe.kext + KS - 1) / KS;
-  if (steps > 1) pipeline_barrier<NL>();
-  else pipeline_barrier<0>();
+  first_barrier<D, NL>(steps < D ? steps : D);
   Frags<T> f0, f1;
   Wide<T> w0, w1;
   read_frags<T, LO, HI>(f0, lds, 0, wm, wn, lane);
   widen_slice<T, LO>(w0, f0, 0);
   int st = 0, kt = 0;
-  for (; kt + 3 < steps; ++kt) {  // copies of full steps only
-    k_iteration<T, LO, HI, 1, true>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
-    st = st == 2 ? 0 : st + 1;
+  for (; kt + D + 1 < steps; ++kt) {  // steady state: copies of full steps only, D - 1 steps in flight at the barrier
+    k_iteration<T, LO, HI, 1, D - 1, true>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
+    st = st == T::NS - 1 ? 0 : st + 1;
   }
-  if (kt + 2 < steps) {  // enqueues the last step, which may be partial
-    k_iteration<T, LO, HI, 2, true>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
-    st = st == 2 ? 0 : st + 1;
-    ++kt;
-  }
-  if (kt + 1 < steps) {
-    k_iteration<T, LO, HI, 0, true>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
-    st = st == 2 ? 0 : st + 1;
-    ++kt;
-  }
-  k_iteration<T, LO, HI, 0, false>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
+  k_loop_tail<T, LO, HI, D>(pipe, lds, steps, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
   __syncthreads();  // the stages are reused by the next loop / the epilogue
 }
 
@@ -864,6 +891,9 @@ int launch_skinny(const GemmArgs& g, hipStream_t st) {
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
+// Three stages everywhere: a fourth stage for the 128x256 tile (exactly the 160 KB of LDS) and four or six for
+// the 64x64 tile were timed and change nothing (c3: 680 us either way on dense random operands; 64 tokens:
+// 55.7 / 60.4 us against 56.8 us) -- the copies are not what the loop waits for.
 typedef Tile<128, 256> Big;   // matrix-core bound shapes
 typedef Tile<64, 64> Skinny;  // M <= 64 (decode): bound by streaming the INT4 weights once from HBM, so the
                               // tile is narrow in N to spread the weight rows over every compute unit
