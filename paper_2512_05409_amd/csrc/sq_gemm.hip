@@ -25,12 +25,14 @@ namespace sq {
 namespace {
 
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int KS = 128;  // channels per K step
 #ifndef SQ_HUGE_MIN_TILES
 #define SQ_HUGE_MIN_TILES 512
 #endif
-constexpr int kHugeMinTiles = SQ_HUGE_MIN_TILES;  // 256x256 tiles a single-product shape needs to use them
+constexpr int kHugeMinTiles = SQ_HUGE_MIN_TILES;
+  // 256x256 tiles a single-product shape needs to use them
 constexpr int NT = 256;  // threads per workgroup
 
 // WITH_LO = false: a tile for loops without a packed low operand (the single-product modes), whose stage
@@ -294,11 +296,11 @@ __device__ __forceinline__ void k_iteration(const Pipe<T, LO, HI>& pipe, char* l
 // k_loop_start enqueues the first NS - 1 steps; k_loop expects them enqueued (whatever independent work the
 // caller has goes between the two calls, under the latency of those first copies).
 template <typename T, bool LO, bool HI>
-__device__ __forceinline__ void k_loop_start(const Pipe<T, LO, HI>& pipe, char* lds) {
-  pipe.template issue<true>(lds, 0);
+__device__ __forceinline__ void k_loop_start(const Pipe<T, LO, HI>& pipe, char* lds, int st0 = 0) {
+  pipe.template issue<true>(lds + st0 * T::STAGE, 0);
 #pragma unroll
   for (int s0 = 1; s0 < T::NS - 1; ++s0)
-    if (pipe.kext > s0 * KS) pipe.template issue<true>(lds + s0 * T::STAGE, s0);
+    if (pipe.kext > s0 * KS) pipe.template issue<true>(lds + ((st0 + s0) % T::NS) * T::STAGE, s0);
 }
 
 // The last iterations of a K loop, peeled: with R steps left after the current one, the iteration that still
@@ -333,16 +335,16 @@ __device__ __forceinline__ void first_barrier(int in_flight) {  // in_flight ste
 
 template <typename T, bool LO, bool HI>
 __device__ __forceinline__ void k_loop(const Pipe<T, LO, HI>& pipe, char* lds, int wm, int wn, int lane,
-                                       v16i (&acc_lo)[T::TI][T::TJ], v16i (&acc_hi)[T::TI][T::TJ]) {
+                                       v16i (&acc_lo)[T::TI][T::TJ], v16i (&acc_hi)[T::TI][T::TJ], int st0 = 0) {
   constexpr int NL = Pipe<T, LO, HI>::NLOAD;
   constexpr int D = T::NS - 1;
   const int steps = (pipe.kext + KS - 1) / KS;
   first_barrier<D, NL>(steps < D ? steps : D);
   Frags<T> f0, f1;
   Wide<T> w0, w1;
-  read_frags<T, LO, HI>(f0, lds, 0, wm, wn, lane);
+  read_frags<T, LO, HI>(f0, lds + st0 * T::STAGE, 0, wm, wn, lane);
   widen_slice<T, LO>(w0, f0, 0);
-  int st = 0, kt = 0;
+  int st = st0, kt = 0;
   for (; kt + D + 1 < steps; ++kt) {  // steady state: copies of full steps only, D - 1 steps in flight at the barrier
     k_iteration<T, LO, HI, 1, D - 1, true>(pipe, lds, kt, st, wm, wn, lane, f0, f1, w0, w1, acc_lo, acc_hi);
     st = st == T::NS - 1 ? 0 : st + 1;
@@ -365,9 +367,8 @@ __device__ __forceinline__ void wave_lds_fence() {
 // Maps the linear workgroup id to a tile so that (a) the workgroups resident on one XCD at a time
 // (ids congruent mod 8 go to the same XCD) cover a compact 4 x 8 patch of tiles and share operand
 // tiles in that XCD's L2, and (b) every XCD walks its own contiguous range of the tile order.
-__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn) {
+__device__ __forceinline__ void tile_of_block(int id, int tiles_m, int tiles_n, int& tm, int& tn) {
   const int total = tiles_m * tiles_n;
-  const int id = blockIdx.x;
   const int per_xcd = (total + 7) / 8;
   const int lin = (id & 7) * per_xcd + (id >> 3);  // position in the tile order
   if (lin >= total) {  // the grid is rounded up to a multiple of 8: the overhang does nothing
@@ -427,7 +428,8 @@ __device__ __forceinline__ void epilogue_typed(const GemmArgs& g, const EpiScale
     sc[tid] = es.slo;
     sc[T::BM + tid] = es.shi;
   }
-  __syncthreads();
+  // workgroup barrier without the memory fence of __syncthreads(): only LDS traffic has to be ordered here
+  pipeline_barrier<63>();
   const bool vec_ok = (g.ldy % PER16) == 0;  // rows of Y stay 16-byte aligned
   OutT* yout = reinterpret_cast<OutT*>(g.y);
 #pragma unroll
@@ -435,10 +437,12 @@ __device__ __forceinline__ void epilogue_typed(const GemmArgs& g, const EpiScale
 #pragma unroll
     for (int rq = 0; rq < 4; ++rq) {
       const int rl0 = 8 * rq + 4 * (lane >> 5);  // 4 consecutive rows of the 32: registers 4 rq + e
-      const float4 slo4 = *reinterpret_cast<const float4*>(sc + wm * T::WM + i * 32 + rl0);
-      const float4 shi4 = *reinterpret_cast<const float4*>(sc + T::BM + wm * T::WM + i * 32 + rl0);
-      const float slo[4] = {slo4.x, slo4.y, slo4.z, slo4.w};
-      const float shi[4] = {shi4.x, shi4.y, shi4.z, shi4.w};
+      // (clang vector types, not HIP's float4: the compiler orders reads of the latter after every LDS-direct
+      // load in flight with a full vmcnt(0) wait)
+      const f32x4 slo4 = *reinterpret_cast<const f32x4*>(sc + wm * T::WM + i * 32 + rl0);
+      const f32x4 shi4 = *reinterpret_cast<const f32x4*>(sc + T::BM + wm * T::WM + i * 32 + rl0);
+      const float slo[4] = {slo4[0], slo4[1], slo4[2], slo4[3]};
+      const float shi[4] = {shi4[0], shi4[1], shi4[2], shi4[3]};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
 #pragma unroll
@@ -462,7 +466,11 @@ __device__ __forceinline__ void epilogue_typed(const GemmArgs& g, const EpiScale
       if (m < g.M && n < g.N) {
         OutT* dst = yout + static_cast<int64_t>(m) * g.ldy + n;
         if (vec_ok && n + PER16 <= g.N) {
-          *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(tb + rl * ROW + ch * 16);
+          // streaming store (nt): Y is written once and not read by this kernel; measured 2 % on the
+          // single-product kernel, neutral on the two-product one.  Written as asm, so the two idle slots a
+          // wide store needs before its data registers may be overwritten are added by hand.
+          const v4u vv = *reinterpret_cast<const v4u*>(tb + rl * ROW + ch * 16);
+          asm volatile("global_store_dwordx4 %0, %1, off nt\n\ts_nop 1" ::"v"(dst), "v"(vv) : "memory");
         } else {  // ragged right edge or unaligned rows: element by element, straight from LDS
           const OutT* src = reinterpret_cast<const OutT*>(tb + rl * ROW + ch * 16);
           for (int q = 0; q < PER16 && n + q < g.N; ++q) dst[q] = src[q];
@@ -505,7 +513,7 @@ __global__ __launch_bounds__(NT) void gemm_kernel(GemmArgs g) {
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   int tm, tn;
-  tile_of_block((g.M + T::BM - 1) / T::BM, (g.N + T::BN - 1) / T::BN, tm, tn);
+  tile_of_block(blockIdx.x, (g.M + T::BM - 1) / T::BM, (g.N + T::BN - 1) / T::BN, tm, tn);
   if (tm < 0) return;
   const int m0 = tm * T::BM, n0 = tn * T::BN;
 
