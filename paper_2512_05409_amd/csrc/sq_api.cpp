@@ -10,7 +10,16 @@
 namespace sq {
 
 // The only process-wide state of the library: one flag per device saying that the kernels' dynamic-LDS
-// limits have been raised and the scratch array of sq_linear_noalloc has been located there.
+// limits have been raised and the scratch array of sq_linear_noalloc has been located there (and, with it,
+// the device's number of compute units, which the encoders size their grids by).
+static int g_compute_units[64];  // written once per device under the mutex below, read after the acquire load
+
+int device_compute_units() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64 || g_compute_units[dev] <= 0) return 256;
+  return g_compute_units[dev];
+}
+
 int ensure_device_ready() {
   static std::atomic<int> ready[64];
   static std::mutex mu;
@@ -19,6 +28,8 @@ int ensure_device_ready() {
   if (ready[dev].load(std::memory_order_acquire)) return SQ_OK;
   std::lock_guard<std::mutex> lock(mu);
   if (ready[dev].load(std::memory_order_relaxed)) return SQ_OK;
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) g_compute_units[dev] = cus;
   int rc = init_gemm_kernels();
   if (rc == SQ_OK) rc = init_encode_kernels();
   if (rc == SQ_OK) rc = init_scratch(dev);

@@ -18,6 +18,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 // ---- per-device initialisation (sq_api.cpp): raises the dynamic-LDS limits of the kernels and looks up
 // the address of the no-allocation scratch array, once per device; every launching entry point calls it. ----
 int ensure_device_ready();
+int device_compute_units();  // of the current device (recorded by ensure_device_ready)
 int init_gemm_kernels();     // sq_gemm.hip
 int init_encode_kernels();   // sq_encode.hip
 int init_scratch(int dev);   // sq_noalloc.hip

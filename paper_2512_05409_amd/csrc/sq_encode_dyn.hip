@@ -418,11 +418,7 @@ template <int B, int KT, bool TIED>
 int launch_stream_t(const StreamArgs& a, hipStream_t st) {
   typedef StreamCfg<B> C;
   const int64_t groups = (a.units + C::NW - 1) / C::NW;
-  int dev = 0, cus = 256;
-  if (hipGetDevice(&dev) == hipSuccess) {
-    int v = 0;
-    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
-  }
+  const int cus = device_compute_units();
   const int resident = 160 * 1024 / C::LDS_BYTES;  // workgroups a compute unit holds at once
   const int64_t cap = static_cast<int64_t>(cus) * resident;
   const int blocks = static_cast<int>(groups < cap ? groups : cap);

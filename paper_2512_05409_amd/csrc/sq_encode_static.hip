@@ -264,11 +264,7 @@ int launch_encode_static_gather(const sq_params& p, const uint16_t* x, int64_t l
   a.q_lo = code_max(p.h_low, 4);
   a.row_bytes_padded = static_cast<int>((static_cast<size_t>(p.K) * 2 + 4095) / 4096 * 4096);
   const size_t lds = gather_lds_bytes(p.K);
-  int dev = 0, cus = 256;
-  if (hipGetDevice(&dev) == hipSuccess) {
-    int v = 0;
-    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
-  }
+  const int cus = device_compute_units();
   int per_cu = static_cast<int>(160 * 1024 / (lds + 256));
   if (per_cu < 1) per_cu = 1;
   if (per_cu > 4) per_cu = 4;
