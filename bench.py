@@ -32,9 +32,9 @@ HBM_PEAK_GBS = 8000.0    # MI355X HBM3E peak, GB/s
 # device copy of known size (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Counters cannot be read from inside
 # this process, so the figures are the recorded ones; they apply to the unmodified workload shapes only.
 MEASURED_GEMM_TRAFFIC = {
-    "c3": {"fetch_bytes": 647.9e6, "write_bytes": 222.6e6, "source": "profiles/sq_linear_c3_mlp7b.md"},
-    "c4": {"fetch_bytes": 237.5e6, "write_bytes": 44.6e6, "source": "profiles/sq_linear_c4_down7b_static.md"},
-    "c5": {"fetch_bytes": 3317.4e6, "write_bytes": 579.9e6, "source": "profiles/sq_linear_c5_up70b.md"},
+    "c3": {"fetch_bytes": 642.3e6, "write_bytes": 211.4e6, "source": "profiles/sq_linear_c3_mlp7b.md"},
+    "c4": {"fetch_bytes": 236.6e6, "write_bytes": 40.4e6, "source": "profiles/sq_linear_c4_down7b_static.md"},
+    "c5": {"fetch_bytes": 3302.5e6, "write_bytes": 550.5e6, "source": "profiles/sq_linear_c5_up70b.md"},
 }
 
 WORKLOADS = {
