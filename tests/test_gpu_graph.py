@@ -13,8 +13,11 @@ from gpu_util import dev
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("M,mode", [(8, "dynamic"), (200, "dynamic"), (48, "static")])
-def test_sq_linear_under_graph_capture(M, mode):
+@pytest.mark.parametrize("M,mode,noalloc", [(8, "dynamic", False), (200, "dynamic", False), (48, "static", False),
+                                             (300, "tied", False), (24, "dynamic", True), (150, "static", True)])
+def test_sq_linear_under_graph_capture(M, mode, noalloc):
+    """noalloc: the captured call is sq_linear_noalloc (its workspace is the library's fixed device array: the
+    form of the layer for code that may not allocate, such as a capture)."""
     K, N, bank, topk = 1024, 384, 64, 8
     rng = np.random.Generator(np.random.PCG64([M, 99]))
     xs = [workloads.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32) * (1 + 20 * (rng.random((1, K)) < 0.02)))
@@ -22,7 +25,8 @@ def test_sq_linear_under_graph_capture(M, mode):
     wq = workloads.pack_int4(rng.integers(-8, 8, size=(N, K), dtype=np.int8))
     sw = rng.uniform(0.005, 0.02, size=N).astype(np.float32)
     static = mode == "static"
-    p = sq.params(M, K, N, bank, topk, mode=sq.SQ_STATIC if static else sq.SQ_DYNAMIC, out_dtype=sq.SQ_OUT_F32)
+    lib_mode = {"dynamic": sq.SQ_DYNAMIC, "static": sq.SQ_STATIC, "tied": sq.SQ_DYNAMIC_TIED}[mode]
+    p = sq.params(M, K, N, bank, topk, mode=lib_mode, out_dtype=sq.SQ_OUT_F32)
     wqd, swd = dev(wq), dev(sw)
     md, pre = None, None
     if static:
@@ -54,7 +58,10 @@ def test_sq_linear_under_graph_capture(M, mode):
         x_static.copy_(dev(xs[0]))
         side.synchronize()
         with torch.cuda.graph(graph, stream=side):
-            sq.sq_linear(p, x_static, w, y_graph, ws, static_mask=md, stream=side)
+            if noalloc:
+                sq.sq_linear_noalloc(p, x_static, w, y_graph, static_mask=md, stream=side)
+            else:
+                sq.sq_linear(p, x_static, w, y_graph, ws, static_mask=md, stream=side)
     torch.cuda.synchronize()
 
     for rep in range(2):
