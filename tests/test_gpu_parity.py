@@ -374,3 +374,60 @@ def test_hi_dense_image_from_encoder_and_from_gemm_workspace(K, bank, topk):
     assert np.array_equal(ws[:M * K].cpu().numpy().view(np.int8).reshape(M, K), want)
     assert torch.equal(y1, y2)
     assert np.array_equal(y1.cpu().numpy().reshape(M, N).view(np.uint32), oracle.gemm(enc, wq, sw).y32.view(np.uint32))
+
+
+@pytest.mark.parametrize("mode", ["dynamic", "tied", "static"])
+def test_encode_padded_rows_of_x_on_the_streaming_kernels(mode):
+    """ldx > K on the kernels that copy rows into LDS (K = 4096: a unit of the streaming kernel lies inside one
+    row; the static kernel stages whole rows): the padding holds +inf and must never be read as data."""
+    _say(f"encode ldx {mode}")
+    M, K, bank, topk, ldx = 70, 4096, 64, 8, 4096 + 24
+    bits, _, _ = random_case(77, M=M, K=K, N=8)
+    if mode == "static":
+        mask = make_static_mask(K, bank, topk, seed=3)
+        p, act = run_encode(bits, bank, topk, static_mask=mask, ldx=ldx)
+        assert_encoding_equal(act, oracle.encode(bits, bank, topk, static_mask=mask))
+        return
+    padded = np.full((M, ldx), 0x7F80, np.uint16)
+    padded[:, :K] = bits
+    lib_mode = sq.SQ_DYNAMIC if mode == "dynamic" else sq.SQ_DYNAMIC_TIED
+    p = sq.params(M, K, 64, bank, topk, mode=lib_mode)
+    act = GuardedAct(p)
+    sq.sq_encode(p, dev(padded), act, ldx=ldx)
+    torch.cuda.synchronize()
+    act.check()
+    assert_encoding_equal(act, oracle.encode(bits, bank, topk) if mode == "dynamic" else oracle.encode_tied(bits, bank, topk))
+
+
+@pytest.mark.parametrize("K,bank,topk", [(28672, 64, 8), (49152, 128, 16)])
+def test_static_long_rows(K, bank, topk):
+    """Static mode on long rows: 28672 channels take the row-staged encoder's larger instantiation and the reordered
+    operands; 49152 channels do not fit in LDS, so sq_linear falls back to the dense low part (and sq_encode
+    refuses lo_compact)."""
+    _say(f"static long rows K={K}")
+    M, N = 9, 96
+    bits, wq, sw = random_case(5100 + K, M, K, N, outliers=8)
+    mask = make_static_mask(K, bank, topk, seed=K)
+    enc = oracle.encode(bits, bank, topk, static_mask=mask)
+    prod = oracle.gemm(enc, wq, sw)
+    p = sq.params(M, K, N, bank, topk, mode=sq.SQ_STATIC, out_dtype=sq.SQ_OUT_F32)
+    xd, wqd, swd, md = dev(bits), dev(wq), dev(sw), dev(mask)
+    pre = torch.empty(sq.sq_weight_prepack_bytes(p), dtype=torch.uint8, device="cuda")
+    sq.sq_weight_prepack(p, wqd, None, md, pre)
+    act = GuardedAct(p, static_mask=md)
+    sq.sq_encode(p, xd, act, static_mask=md)
+    torch.cuda.synchronize()
+    act.check()
+    assert_encoding_equal(act, enc)
+    if K > 40000:
+        act.lo_compact = torch.empty(sq.sq_lo_compact_bytes(p), dtype=torch.uint8, device="cuda")
+        with pytest.raises(sq.SqError) as e:
+            sq.sq_encode(p, xd, act, static_mask=md)
+        assert e.value.status == -3
+    y = Guarded(M * N * 4, torch.float32)
+    ws = Guarded(sq.sq_linear_workspace_bytes(p), torch.uint8)
+    sq.sq_linear(p, xd, sq.weight(wqd, swd, pre), y.t, ws.t, static_mask=md)
+    torch.cuda.synchronize()
+    y.check()
+    ws.check()
+    assert np.array_equal(y.host(np.uint32).reshape(M, N), prod.y32.view(np.uint32))
