@@ -131,6 +131,15 @@ def probes(torch, sq, xs, enc_write_bytes):
         torch.cuda.synchronize()
         rates[random_operands] = 2.0 * 32768 * 8 * iters * 4 * blocks / (e0.elapsed_time(e1) * 1e-3) / 1e12
     mfma_tops = rates[False]
+    alt = {}
+    for kind, name in ((0, "mfma_fp6_e3m2_register_only_tops"), (1, "smfmac_i8_2to4_register_only_dense_equivalent_tops")):
+        sq.sq_probe_mfma_alt(kind, blocks, iters, sink)
+        torch.cuda.synchronize()
+        e0.record()
+        sq.sq_probe_mfma_alt(kind, blocks, iters, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        alt[name] = 2.0 * 65536 * 8 * iters * 4 * blocks / (e0.elapsed_time(e1) * 1e-3) / 1e12
 
     read_bytes = xs[0].numel() * xs[0].element_size()
     write_bytes = (int(enc_write_bytes) + 15) // 16 * 16
@@ -146,7 +155,7 @@ def probes(torch, sq, xs, enc_write_bytes):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / reps
     return {"mfma_i8_register_only_tops": mfma_tops, "mfma_i8_frac_of_peak": mfma_tops / INT8_PEAK_TOPS,
-            "mfma_i8_register_only_random_operands_tops": rates[True],
+            "mfma_i8_register_only_random_operands_tops": rates[True], **alt,
             "stream_encode_mix_gbs": (read_bytes + write_bytes) / (ms * 1e-3) / 1e9,
             "stream_encode_mix_ms": ms, "stream_read_bytes": read_bytes, "stream_write_bytes": write_bytes,
             "note": "sq_probe_mfma_i8: 8 independent v_mfma_i32_32x32x32_i8 per wave per iteration, 2 workgroups per CU, "

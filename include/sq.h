@@ -265,6 +265,17 @@ int sq_calibrate_static(const sq_params *p, const uint16_t *x_calib, int64_t ldx
  *   kernel with the encoder's mix of bytes read and written sustains.
  * Both only enqueue work on `stream`; errors as for the other calls. */
 int sq_probe_mfma_i8(int blocks, int iters, int random_operands, int32_t *sink, void *stream);
+/* The same rate probe for the two other matrix paths of the chip that could carry a part of the layer (Section 3.3:
+ * the split pays when the low-precision path is faster): kind 0 = v_mfma_scale_f32_32x32x64_f8f6f4 on FP6 E3M2
+ * operands (E3M2 holds every INT4 code exactly), kind 1 = v_smfmac_i32_32x32x64_i8 (2:4 structured-sparse INT8);
+ * 2 * 65536 * 8 * iters * 4 * blocks (dense-equivalent) operations per launch.  Arguments as sq_probe_mfma_i8.
+ * sq_probe_fp6_tile: one wave accumulates `reps` products of a 32x64 by 64x32 tile of E3M2 codes on top of c0:
+ *   a, b device, 64 lanes x 32 bytes: lane l holds row (a) / column (b) l % 32, K slots 32*(l/32) ... +31, slot t
+ *   in bits [6t, 6t+6) of the lane's first 24 bytes; c device, 64 lanes x 16 floats: register r of lane l is
+ *   row 8*(r/4) + 4*(l/32) + r%4, column l%32.  32-byte aligned pointers, 1 <= reps <= 2^20.
+ * Used by tests/test_gpu_probes.py to show that integer products are exact on that path while sums stay below 2^24. */
+int sq_probe_mfma_alt(int kind, int blocks, int iters, int32_t *sink, void *stream);
+int sq_probe_fp6_tile(const void *a, const void *b, float *c, float c0, int reps, void *stream);
 int sq_probe_stream(const void *src, size_t read_bytes, void *dst, size_t write_bytes, void *stream);
 
 /* Human-readable name of a status code (static storage, never NULL). */

@@ -23,7 +23,7 @@ EXPORTS = (
     "sq_weight_prepack", "sq_encode", "sq_gemm", "sq_linear", "sq_dense_w4a8_prepack", "sq_dense_w4a8_gemm",
     "sq_calibrate_workspace_bytes", "sq_calibrate_static", "sq_probe_mfma_i8", "sq_probe_stream", "sq_status_string", "sq_version",
     "sq_init", "sq_gemm_variant", "sq_linear_noalloc", "sq_lo_compact_bytes",
-    "sq_storage_row_bytes", "sq_pack_storage", "sq_unpack_storage",
+    "sq_storage_row_bytes", "sq_pack_storage", "sq_unpack_storage", "sq_probe_mfma_alt", "sq_probe_fp6_tile",
 )
 SQ_NOALLOC_SCRATCH_BYTES = 8 << 20
 
@@ -80,6 +80,10 @@ def lib() -> ctypes.CDLL:
         L.sq_calibrate_static.restype = ctypes.c_int
         L.sq_probe_mfma_i8.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
         L.sq_probe_stream.argtypes = [vp, sz, vp, sz, vp]
+        L.sq_probe_mfma_alt.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
+        L.sq_probe_mfma_alt.restype = ctypes.c_int
+        L.sq_probe_fp6_tile.argtypes = [vp, vp, vp, ctypes.c_float, ctypes.c_int, vp]
+        L.sq_probe_fp6_tile.restype = ctypes.c_int
         for f in (L.sq_weight_prepack, L.sq_encode, L.sq_gemm, L.sq_linear, L.sq_dense_w4a8_prepack,
                   L.sq_dense_w4a8_gemm, L.sq_probe_mfma_i8, L.sq_probe_stream):
             f.restype = ctypes.c_int
@@ -281,6 +285,14 @@ def sq_calibrate_static(p: sq_params, x_calib, T: int, w: sq_weight, mask_out, i
 def sq_probe_mfma_i8(blocks: int, iters: int, sink, random_operands: bool = False, stream=None) -> None:
     _check(lib().sq_probe_mfma_i8(int(blocks), int(iters), int(bool(random_operands)), _ptr(sink), _stream(stream)),
            "sq_probe_mfma_i8")
+
+
+def sq_probe_mfma_alt(kind: int, blocks: int, iters: int, sink, stream=None) -> None:
+    _check(lib().sq_probe_mfma_alt(int(kind), int(blocks), int(iters), _ptr(sink), _stream(stream)), "sq_probe_mfma_alt")
+
+
+def sq_probe_fp6_tile(a, b, c, c0: float = 0.0, reps: int = 1, stream=None) -> None:
+    _check(lib().sq_probe_fp6_tile(_ptr(a), _ptr(b), _ptr(c), float(c0), int(reps), _stream(stream)), "sq_probe_fp6_tile")
 
 
 def sq_probe_stream(src, read_bytes: int, dst, write_bytes: int, stream=None) -> None:

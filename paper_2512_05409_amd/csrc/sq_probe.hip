@@ -49,6 +49,84 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(int iters, int32_t* __re
   sink[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+// The two other matrix paths of CDNA4 that could carry a part of the layer, on register operands, as rate probes:
+//  KIND 0: v_mfma_scale_f32_32x32x64_f8f6f4 with FP6 E3M2 operands and unit block scales (E3M2 holds every integer
+//          of [-8, 8], so INT4 x INT4 products and their fp32 sums below 2^24 are exact): 2*32*32*64 operations each;
+//  KIND 1: v_smfmac_i32_32x32x64_i8, the 2:4 structured-sparse INT8 instruction (A holds 2 of every 4 K slots):
+//          counted as the 2*32*32*64 operations of the dense product it stands for.
+// Eight independent accumulators per wave; the operands are arbitrary bit patterns (rates only).
+template <int KIND>
+__global__ __launch_bounds__(256) void alt_rate_kernel(int iters, int32_t* __restrict__ sink) {
+  unsigned x = 0x9E3779B9u * (blockIdx.x * 256 + threadIdx.x + 1);
+  v8i a[8], b[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      x = x * 1664525u + 1013904223u;
+      a[i][q] = static_cast<int>(x & 0x1F7DF7DFu);  // FP6: exponent fields kept below the maximum (finite values)
+      x = x * 1664525u + 1013904223u;
+      b[i][q] = static_cast<int>(x & 0x1F7DF7DFu);
+    }
+  int s = 0;
+  if constexpr (KIND == 0) {
+    v16f acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+    for (int it = 0; it < iters; it += 8) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[(i + u) & 7], acc[i], 3, 3, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s += static_cast<int>(acc[i][r] != 0.0f);
+  } else {
+    v16i acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+    for (int it = 0; it < iters; it += 8) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const v4i as = {a[i][0], a[i][1], a[i][2], a[i][3]};
+          acc[i] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(as, b[(i + u) & 7], acc[i], 0x44444444, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s += acc[i][r];
+  }
+  sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+// One 32x32x64 product on the FP6 path, for checking its exactness on integer operands: lane l holds row (A) /
+// column (B) l % 32 and the 32 K slots 32*(l/32) ... +31 as 6-bit E3M2 codes, slot t in bits [6t, 6t+6) of its
+// eight dwords; accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32.  reps products are
+// accumulated on top of c0.
+__global__ __launch_bounds__(64) void fp6_tile_kernel(const v8i* __restrict__ a, const v8i* __restrict__ b,
+                                                      v16f* __restrict__ c, float c0, int reps) {
+  v16f acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = c0;
+  const v8i av = a[threadIdx.x], bv = b[threadIdx.x];
+  for (int i = 0; i < reps; ++i)
+    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, acc, 3, 3, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
+  c[threadIdx.x] = acc;
+}
+
 // Reads n_read 16-byte chunks and writes n_write chunks, both coalesced, grid-stride.
 __global__ __launch_bounds__(256) void stream_kernel(const v4u* __restrict__ src, int64_t n_read, v4u* __restrict__ dst,
                                                      int64_t n_write) {
@@ -68,6 +146,27 @@ extern "C" int sq_probe_mfma_i8(int blocks, int iters, int random_operands, int3
     hipLaunchKernelGGL(mfma_rate_kernel<true>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), iters, sink);
   else
     hipLaunchKernelGGL(mfma_rate_kernel<false>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), iters, sink);
+  return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+extern "C" int sq_probe_mfma_alt(int kind, int blocks, int iters, int32_t* sink, void* stream) {
+  if (!sink) return SQ_ERR_NULL;
+  if (blocks <= 0 || blocks > 65536 || iters <= 0 || iters % 8) return SQ_ERR_SHAPE;
+  if (kind == 0)
+    hipLaunchKernelGGL(alt_rate_kernel<0>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), iters, sink);
+  else if (kind == 1)
+    hipLaunchKernelGGL(alt_rate_kernel<1>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), iters, sink);
+  else
+    return SQ_ERR_UNSUPPORTED;
+  return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+extern "C" int sq_probe_fp6_tile(const void* a, const void* b, float* c, float c0, int reps, void* stream) {
+  if (!a || !b || !c) return SQ_ERR_NULL;
+  if (reps <= 0 || reps > (1 << 20)) return SQ_ERR_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b) | reinterpret_cast<uintptr_t>(c)) & 31) return SQ_ERR_ALIGN;
+  hipLaunchKernelGGL(fp6_tile_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), static_cast<const v8i*>(a),
+                     static_cast<const v8i*>(b), reinterpret_cast<v16f*>(c), c0, reps);
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
