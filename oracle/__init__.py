@@ -243,3 +243,16 @@ def unpack_storage(packed, mask, K, bank, topk, h_high, h_low, s_lo, s_hi, stati
 
 def storage_row_bytes(K, bank, topk, h_high, h_low):
     return _pairs().storage_row_bytes(K, bank, topk, h_high, h_low)
+
+
+def pack_storage_sentinel(enc, h_high, h_low):
+    """The implicit-mask form: K*x/8 bytes per row, x = (1-s) h_high + h_low, sentinels at the high channels."""
+    return _pairs().pack_storage_sentinel(enc, h_high, h_low)
+
+
+def unpack_storage_sentinel(packed, K, bank, topk, h_high, h_low, s_lo, s_hi):
+    return _pairs().unpack_storage_sentinel(packed, K, bank, topk, h_high, h_low, s_lo, s_hi)
+
+
+def sentinel_row_bytes(K, bank, topk, h_high, h_low):
+    return _pairs().sentinel_row_bytes(K, bank, topk, h_high, h_low)

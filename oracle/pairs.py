@@ -19,6 +19,14 @@ the LOW channels only at h_low bits each, both in ascending channel order, as on
 section (code t occupies bits [t*h, (t+1)*h) of its section; bit i of a section is bit i%8 of its byte i/8;
 h-bit two's complement).  Row size = K * y / 8 bytes exactly; the mask and the two scales are stored beside it.
 
+pack_storage_sentinel / unpack_storage_sentinel: the implicit-mask form of Section 3.1 / Section 3.2.1 ("the unused
+largest value of the low-precision format is considered as a high-precision mask"): the low section covers ALL K
+channels and holds, at the high channels, the code the symmetric range leaves unused, v_mask = -2^(h_low-1)
+(bit pattern 10 = 2 for INT2, as in the paper's example; for INT4 the pattern is 1000 -- the figure caption's
+"15" does not fit two's complement, reading taken: the one consistent with the INT2 example); no mask is stored,
+unpacking recovers it from the sentinels.  Row size = K * x / 8 bytes with x = (1-s)*h_high + h_low, the
+formula Section 4.1 gives for this form.
+
 Pins (tests/test_oracle_pairs.py): for (8/4) encode_pair must equal the pinned C oracle bit for bit; hand-built
 rows with scale 1 for Q = 3 and Q = 1 including half-way cases; code ranges; storage size against the y column
 of the paper's Table 3 (tests/golden); pack/unpack round trip and a hand-packed 3-bit example; planted mistakes.
@@ -115,6 +123,46 @@ def pack_storage(enc: Encoded, h_high: int, h_low: int) -> np.ndarray:
         out[m, : len(hs)] = hs
         out[m, len(hs):] = ls
     return out
+
+
+def sentinel_row_bytes(K: int, bank: int, topk: int, h_high: int, h_low: int) -> int:
+    return (K // bank * topk * h_high + K * h_low) // 8
+
+
+def pack_storage_sentinel(enc: Encoded, h_high: int, h_low: int) -> np.ndarray:
+    """-> [M, K*x/8] bytes: high section, then K low codes with v_mask = -2^(h_low-1) at the high channels."""
+    flags = _flags(enc)
+    d = _low_codes(enc)
+    v_mask = -(1 << (h_low - 1))
+    out = np.zeros((enc.M, sentinel_row_bytes(enc.K, enc.bank, enc.topk, h_high, h_low)), np.uint8)
+    for m in range(enc.M):
+        hs = _pack_section(enc.hi_val[m].reshape(-1), h_high)
+        ls = _pack_section(np.where(flags[m], v_mask, d[m]), h_low)
+        out[m, : len(hs)] = hs
+        out[m, len(hs):] = ls
+    return out
+
+
+def unpack_storage_sentinel(packed: np.ndarray, K: int, bank: int, topk: int, h_high: int, h_low: int,
+                            s_lo: np.ndarray, s_hi: np.ndarray) -> Encoded:
+    """The inverse; the (per-row) mask comes out of the sentinels."""
+    M = packed.shape[0]
+    G = K // bank
+    k_hi = G * topk
+    nh = k_hi * h_high // 8
+    v_mask = -(1 << (h_low - 1))
+    d_lo = np.zeros((M, K // 2), np.uint8)
+    hi_val = np.zeros((M, G, topk), np.int8)
+    mask = np.zeros((M, K // 32), np.uint32)
+    for m in range(M):
+        hi_val[m] = _unpack_section(packed[m, :nh], k_hi, h_high).reshape(G, topk)
+        d = _unpack_section(packed[m, nh:], K, h_low)
+        is_hi = d == v_mask
+        d = np.where(is_hi, 0, d)
+        d_lo[m] = ((d[0::2] & 0xF) | ((d[1::2] & 0xF) << 4)).astype(np.uint8)
+        bits = is_hi.reshape(K // 32, 32).astype(np.uint64) << np.arange(32, dtype=np.uint64)[None, :]
+        mask[m] = bits.sum(1).astype(np.uint32)
+    return Encoded(M, K, bank, topk, 0, d_lo, hi_val, mask, s_lo, s_hi)
 
 
 def unpack_storage(packed: np.ndarray, mask: np.ndarray, K: int, bank: int, topk: int, h_high: int, h_low: int,

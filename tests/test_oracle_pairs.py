@@ -113,6 +113,30 @@ def test_pack_by_hand_and_round_trip():
         assert np.array_equal(back.d_lo, enc.d_lo) and np.array_equal(back.hi_val, enc.hi_val)
 
 
+def test_sentinel_form_by_hand_and_round_trip():
+    # (8/2), one bank of 32 inside K = 64 (k = 4): low codes are -1, 0, 1; the high channels carry v_mask = -2
+    # (bit pattern 10).  Channels 0..3 high; low codes of channels 4.. : 1, -1, 0, 1 -> 2-bit patterns 01, 11, 00, 01.
+    # first low byte = channels 0..3 = four sentinels: 10 10 10 10 -> bits (LSB first) 0,1,0,1,0,1,0,1 -> 0xAA
+    # second byte = channels 4..7: 01, 11, 00, 01 -> bits 1,0, 1,1, 0,0, 1,0 -> 0x4D
+    vals = [127, -64, 100, 90, 1, -1, 0.2, 1]
+    enc = oracle.encode_pair(row_with(vals, K=64), 32, 4, 8, 2)
+    assert list(unpack_int4(enc.d_lo)[0, :8]) == [0, 0, 0, 0, 1, -1, 0, 1]
+    p = oracle.pack_storage_sentinel(enc, 8, 2)
+    assert p.shape == (1, 8 + 64 * 2 // 8)
+    assert [int(v) for v in p[0, 8:10]] == [0xAA, 0x4D]
+    # storage of this form: x = (1-s)*h_high + h_low bits per element (Section 4.1)
+    for h_high, h_low in PAIRS:
+        for bank, topk in ((64, 8), (32, 16), (128, 16)):
+            s = 1 - topk / bank
+            assert oracle.sentinel_row_bytes(4096, bank, topk, h_high, h_low) * 8 == 4096 * ((1 - s) * h_high + h_low)
+        wl = make("c1_tiny")
+        enc = oracle.encode_pair(wl.x_bits, wl.bank, wl.topk, h_high, h_low)
+        packed = oracle.pack_storage_sentinel(enc, h_high, h_low)
+        back = oracle.unpack_storage_sentinel(packed, wl.K, wl.bank, wl.topk, h_high, h_low, enc.s_lo, enc.s_hi)
+        assert np.array_equal(back.mask, enc.mask), "the mask must come back out of the sentinels"
+        assert np.array_equal(back.d_lo, enc.d_lo) and np.array_equal(back.hi_val, enc.hi_val)
+
+
 SOURCE = open(os.path.join(ROOT, "oracle", "pairs.py")).read()
 MUTANTS = [
     ("code range 2^(h-1) instead of 2^(h-1)-1", "return (1 << (bits - 1)) - 1", "return 1 << (bits - 1)"),
@@ -122,6 +146,8 @@ MUTANTS = [
     ("low codes kept at high channels", "        d[is_hi] = 0\n", ""),
     ("bit stream is MSB first", 'return np.packbits(bits, bitorder="little")', 'return np.packbits(bits, bitorder="big")'),
     ("storage counts the low part over all channels", "return (k_hi * h_high + (K - k_hi) * h_low) // 8", "return (k_hi * h_high + K * h_low) // 8"),
+    ("sentinel is the largest positive code", "v_mask = -(1 << (h_low - 1))\n    out = np.zeros", "v_mask = (1 << (h_low - 1)) - 1\n    out = np.zeros"),
+    ("sentinel form keeps the low codes at the high channels", "ls = _pack_section(np.where(flags[m], v_mask, d[m]), h_low)", "ls = _pack_section(d[m], h_low)"),
     ("low section packs the high channels too", "ls = _pack_section(d[m][~flags[m]], h_low)", "ls = _pack_section(d[m], h_low)[: out.shape[1] - len(hs)]"),
 ]
 
