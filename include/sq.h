@@ -130,6 +130,14 @@ typedef struct {
 size_t sq_storage_row_bytes(const sq_params *p);
 int sq_pack_storage(const sq_params *p, const sq_act *a, uint8_t *packed, void *stream);
 int sq_unpack_storage(const sq_params *p, const uint8_t *packed, const sq_act *a, void *stream);
+/* The implicit-mask form (Section 3.1: the mask "represented implicitly by low-precision parts"; Section 3.2.1: the
+ * code the symmetric low format leaves unused marks a high-precision element): the low section covers ALL K
+ * channels and holds v_mask = -2^(h_low-1) at the high channels; no mask is stored, sq_unpack_storage_sentinel
+ * writes it to a->mask (dynamic layout [M, K/32]) together with d_lo and hi_val.  K*x/8 bytes per row,
+ * x = (1-s)*h_high + h_low (Section 4.1).  Dynamic modes only (SQ_ERR_UNSUPPORTED in static mode). */
+size_t sq_storage_row_bytes_sentinel(const sq_params *p);
+int sq_pack_storage_sentinel(const sq_params *p, const sq_act *a, uint8_t *packed, void *stream);
+int sq_unpack_storage_sentinel(const sq_params *p, const uint8_t *packed, const sq_act *a, void *stream);
 
 /* Per-device initialisation for the current device (idempotent, thread-safe): raises the kernels' dynamic-LDS
  * limits.  Every launching entry point does this on its first call on a device; call it explicitly before a

@@ -24,6 +24,7 @@ EXPORTS = (
     "sq_calibrate_workspace_bytes", "sq_calibrate_static", "sq_probe_mfma_i8", "sq_probe_stream", "sq_status_string", "sq_version",
     "sq_init", "sq_gemm_variant", "sq_linear_noalloc", "sq_lo_compact_bytes",
     "sq_storage_row_bytes", "sq_pack_storage", "sq_unpack_storage", "sq_probe_mfma_alt", "sq_probe_fp6_tile",
+    "sq_storage_row_bytes_sentinel", "sq_pack_storage_sentinel", "sq_unpack_storage_sentinel",
 )
 SQ_NOALLOC_SCRATCH_BYTES = 8 << 20
 
@@ -94,6 +95,12 @@ def lib() -> ctypes.CDLL:
         L.sq_storage_row_bytes.restype = sz
         L.sq_pack_storage.argtypes = [P(sq_params), P(sq_act), vp, vp]
         L.sq_unpack_storage.argtypes = [P(sq_params), vp, P(sq_act), vp]
+        L.sq_storage_row_bytes_sentinel.argtypes = [P(sq_params)]
+        L.sq_storage_row_bytes_sentinel.restype = sz
+        L.sq_pack_storage_sentinel.argtypes = [P(sq_params), P(sq_act), vp, vp]
+        L.sq_unpack_storage_sentinel.argtypes = [P(sq_params), vp, P(sq_act), vp]
+        L.sq_pack_storage_sentinel.restype = ctypes.c_int
+        L.sq_unpack_storage_sentinel.restype = ctypes.c_int
         L.sq_pack_storage.restype = ctypes.c_int
         L.sq_unpack_storage.restype = ctypes.c_int
         L.sq_init.argtypes = []
@@ -264,6 +271,22 @@ def sq_pack_storage(p: sq_params, a: Act, packed, stream=None) -> None:
 def sq_unpack_storage(p: sq_params, packed, a: Act, stream=None) -> None:
     ac = a.c()
     _check(lib().sq_unpack_storage(ctypes.byref(p), _ptr(packed), ctypes.byref(ac), _stream(stream)), "sq_unpack_storage")
+
+
+def sq_storage_row_bytes_sentinel(p: sq_params) -> int:
+    return int(lib().sq_storage_row_bytes_sentinel(ctypes.byref(p)))
+
+
+def sq_pack_storage_sentinel(p: sq_params, a: Act, packed, stream=None) -> None:
+    ac = a.c()
+    _check(lib().sq_pack_storage_sentinel(ctypes.byref(p), ctypes.byref(ac), _ptr(packed), _stream(stream)),
+           "sq_pack_storage_sentinel")
+
+
+def sq_unpack_storage_sentinel(p: sq_params, packed, a: Act, stream=None) -> None:
+    ac = a.c()
+    _check(lib().sq_unpack_storage_sentinel(ctypes.byref(p), _ptr(packed), ctypes.byref(ac), _stream(stream)),
+           "sq_unpack_storage_sentinel")
 
 
 def sq_dense_w4a8_prepack(p: sq_params, wq, out, stream=None) -> None:

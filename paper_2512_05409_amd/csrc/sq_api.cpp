@@ -342,21 +342,36 @@ size_t sq_storage_row_bytes(const sq_params* p) {
   return static_cast<size_t>(k_hi_of(p)) * hh / 8 + static_cast<size_t>(p->K - k_hi_of(p)) * hl / 8;
 }
 
-static int storage_call(const sq_params* p, const sq_act* a, uint8_t* packed, bool pack, void* stream) {
+size_t sq_storage_row_bytes_sentinel(const sq_params* p) {
+  if (check_params(p) != SQ_OK || p->mode == SQ_STATIC) return 0;
+  const int hh = p->h_high ? p->h_high : 8, hl = p->h_low ? p->h_low : 4;
+  return static_cast<size_t>(k_hi_of(p)) * hh / 8 + static_cast<size_t>(p->K) * hl / 8;
+}
+
+static int storage_call(const sq_params* p, const sq_act* a, uint8_t* packed, bool pack, bool sentinel, void* stream) {
   int rc = check_params(p);
   if (rc != SQ_OK) return rc;
+  if (sentinel && p->mode == SQ_STATIC) return SQ_ERR_UNSUPPORTED;  // a shared channel mask needs no sentinels
   if (!a || !a->d_lo || !a->hi_val || !a->mask || !packed) return SQ_ERR_NULL;
   if (!aligned16(a->d_lo) || !aligned16(a->hi_val) || !aligned16(a->mask)) return SQ_ERR_ALIGN;
   if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
-  return sq::launch_storage(*p, *a, packed, pack, static_cast<hipStream_t>(stream));
+  return sq::launch_storage(*p, *a, packed, pack, sentinel, static_cast<hipStream_t>(stream));
 }
 
 int sq_pack_storage(const sq_params* p, const sq_act* a, uint8_t* packed, void* stream) {
-  return storage_call(p, a, packed, true, stream);
+  return storage_call(p, a, packed, true, false, stream);
 }
 
 int sq_unpack_storage(const sq_params* p, const uint8_t* packed, const sq_act* a, void* stream) {
-  return storage_call(p, a, const_cast<uint8_t*>(packed), false, stream);
+  return storage_call(p, a, const_cast<uint8_t*>(packed), false, false, stream);
+}
+
+int sq_pack_storage_sentinel(const sq_params* p, const sq_act* a, uint8_t* packed, void* stream) {
+  return storage_call(p, a, packed, true, true, stream);
+}
+
+int sq_unpack_storage_sentinel(const sq_params* p, const uint8_t* packed, const sq_act* a, void* stream) {
+  return storage_call(p, a, const_cast<uint8_t*>(packed), false, true, stream);
 }
 
 int sq_dense_w4a8_prepack(const sq_params* p, const uint8_t* wq, void* out, void* stream) {

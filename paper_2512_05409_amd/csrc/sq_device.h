@@ -59,7 +59,7 @@ int launch_calibrate_static(const sq_params& p, const uint16_t* x, int64_t ldx, 
                             hipStream_t st);
 
 // Pack / unpack the bit-packed storage stream (sq_storage.hip).
-int launch_storage(const sq_params& p, const sq_act& act, uint8_t* packed, bool pack, hipStream_t st);
+int launch_storage(const sq_params& p, const sq_act& act, uint8_t* packed, bool pack, bool sentinel, hipStream_t st);
 
 struct GemmArgs {
   int M, N, K;          // K of the layer

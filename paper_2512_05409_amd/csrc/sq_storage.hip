@@ -14,6 +14,8 @@ struct StoreArgs {
   int row_bytes, hi_bytes;
   int64_t mask_stride;  // words between the masks of consecutive rows (0: one mask for all rows)
   const uint32_t* mask;
+  uint32_t* mask_out;   // sentinel form, unpack: the mask recovered from the sentinels
+  int sentinel;         // 1: the low section covers all K channels and carries v_mask = -2^(hl-1) at the high ones
   uint8_t* d_lo;
   int8_t* hi_val;
   uint8_t* packed;
@@ -52,9 +54,16 @@ __global__ __launch_bounds__(256) void pack_storage_kernel(StoreArgs a) {
     const int bit0 = (b - a.hi_bytes) * 8;  // first bit of this byte inside the low section
     const int nlo = a.B - a.kt;
     const uint32_t cmask = (1u << a.hl) - 1u;
-    for (int t = bit0 / a.hl; t * a.hl < bit0 + 8 && t < a.K_lo; ++t) {
-      const int ch = low_channel(mrow, t / nlo, a.B, t % nlo);
-      const uint32_t code = static_cast<uint32_t>(nibble_at(drow, ch)) & cmask;
+    const int n_codes = a.sentinel ? a.K : a.K_lo;
+    for (int t = bit0 / a.hl; t * a.hl < bit0 + 8 && t < n_codes; ++t) {
+      uint32_t code;
+      if (a.sentinel) {  // code t belongs to channel t; the high channels carry the unused most negative code
+        const bool hi = (mrow[t >> 5] >> (t & 31)) & 1u;
+        code = hi ? (1u << (a.hl - 1)) : (static_cast<uint32_t>(nibble_at(drow, t)) & cmask);
+      } else {
+        const int ch = low_channel(mrow, t / nlo, a.B, t % nlo);
+        code = static_cast<uint32_t>(nibble_at(drow, ch)) & cmask;
+      }
       const int sh = t * a.hl - bit0;
       out |= sh >= 0 ? code << sh : code >> (-sh);
     }
@@ -69,6 +78,38 @@ __device__ __forceinline__ int bits_at(const uint8_t* sec, int n, int o, int h) 
   if (by + 1 < n) v |= static_cast<uint32_t>(sec[by + 1]) << 8;
   v = (v >> (o & 7)) & ((1u << h) - 1u);
   return (v & (1u << (h - 1))) ? static_cast<int>(v) - (1 << h) : static_cast<int>(v);
+}
+
+// Sentinel form: the mask is not stored; a low code equal to v_mask marks a high channel.
+__global__ __launch_bounds__(256) void unpack_sentinel_kernel(StoreArgs a) {
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  const int wpr = a.K / 32;
+  if (idx >= static_cast<int64_t>(a.M) * wpr) return;
+  const int64_t m = idx / wpr;
+  const int wg = static_cast<int>(idx - m * wpr);
+  const int wpb = a.B / 32;
+  const int bank = wg / wpb;
+  const uint8_t* hsec = a.packed + m * a.row_bytes;
+  const uint8_t* lsec = hsec + a.hi_bytes;
+  const int lbytes = a.row_bytes - a.hi_bytes;
+  const int v_mask = -(1 << (a.hl - 1));
+  int nh = 0;  // high channels of the bank before this word
+  for (int ch = bank * a.B; ch < wg * 32; ++ch) nh += bits_at(lsec, lbytes, ch * a.hl, a.hl) == v_mask;
+  int8_t* hv = a.hi_val + m * a.K_hi + bank * a.kt;
+  uint32_t dl[4] = {0, 0, 0, 0};
+  uint32_t word = 0;
+  for (int i = 0; i < 32; ++i) {
+    const int code = bits_at(lsec, lbytes, (wg * 32 + i) * a.hl, a.hl);
+    if (code == v_mask) {
+      word |= 1u << i;
+      if (nh < a.kt) hv[nh] = static_cast<int8_t>(bits_at(hsec, a.hi_bytes, (bank * a.kt + nh) * a.hh, a.hh));
+      ++nh;
+    } else {
+      dl[i >> 3] |= static_cast<uint32_t>(code & 0xF) << (4 * (i & 7));
+    }
+  }
+  a.mask_out[m * wpr + wg] = word;
+  *reinterpret_cast<uint4*>(a.d_lo + m * (a.K / 2) + static_cast<int64_t>(wg) * 16) = make_uint4(dl[0], dl[1], dl[2], dl[3]);
 }
 
 __global__ __launch_bounds__(256) void unpack_storage_kernel(StoreArgs a) {
@@ -106,7 +147,7 @@ __global__ __launch_bounds__(256) void unpack_storage_kernel(StoreArgs a) {
 
 }  // namespace
 
-int launch_storage(const sq_params& p, const sq_act& act, uint8_t* packed, bool pack, hipStream_t st) {
+int launch_storage(const sq_params& p, const sq_act& act, uint8_t* packed, bool pack, bool sentinel, hipStream_t st) {
   StoreArgs a;
   a.M = p.M;
   a.K = p.K;
@@ -118,7 +159,9 @@ int launch_storage(const sq_params& p, const sq_act& act, uint8_t* packed, bool 
   a.K_hi = a.G * p.topk;
   a.K_lo = p.K - a.K_hi;
   a.hi_bytes = a.K_hi * a.hh / 8;
-  a.row_bytes = a.hi_bytes + a.K_lo * a.hl / 8;
+  a.row_bytes = a.hi_bytes + (sentinel ? p.K : a.K_lo) * a.hl / 8;
+  a.sentinel = sentinel ? 1 : 0;
+  a.mask_out = act.mask;
   a.mask_stride = p.mode == SQ_STATIC ? 0 : p.K / 32;
   a.mask = act.mask;
   a.d_lo = act.d_lo;
@@ -127,6 +170,7 @@ int launch_storage(const sq_params& p, const sq_act& act, uint8_t* packed, bool 
   const int64_t total = pack ? static_cast<int64_t>(p.M) * a.row_bytes : static_cast<int64_t>(p.M) * (p.K / 32);
   const unsigned blocks = static_cast<unsigned>((total + 255) / 256);
   if (pack) hipLaunchKernelGGL(pack_storage_kernel, dim3(blocks), dim3(256), 0, st, a);
+  else if (sentinel) hipLaunchKernelGGL(unpack_sentinel_kernel, dim3(blocks), dim3(256), 0, st, a);
   else hipLaunchKernelGGL(unpack_storage_kernel, dim3(blocks), dim3(256), 0, st, a);
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }

@@ -109,3 +109,34 @@ def test_unsupported_pairs_are_refused():
         assert sq.sq_gemm_variant(sq.params(16, 512, 512, h_high=hh, h_low=hl)) == "invalid"
     assert sq.sq_gemm_variant(sq.params(16, 512, 512, mode=sq.SQ_DYNAMIC_TIED, h_high=8, h_low=3)) == "invalid"
     assert sq.sq_gemm_variant(sq.params(16, 512, 512, h_high=8, h_low=3)) != "invalid"
+
+
+@pytest.mark.parametrize("h_high,h_low", PAIRS)
+@pytest.mark.parametrize("M,K,bank,topk", [(19, 1024, 64, 8), (7, 512, 32, 4), (5, 2048, 128, 32)])
+def test_sentinel_storage_stream(M, K, bank, topk, h_high, h_low):
+    """The implicit-mask form: sq_pack_storage_sentinel writes K*x/8 bytes per row equal to the oracle's stream;
+    sq_unpack_storage_sentinel recovers codes AND the mask from it."""
+    _say(f"sentinel storage ({h_high}/{h_low}) M={M} K={K} bank={bank} topk={topk}")
+    bits, _, _ = random_case(4900 + M + K + h_low + bank, M=M, K=K, N=8, outliers=4)
+    enc = oracle.encode_pair(bits, bank, topk, h_high, h_low)
+    want = oracle.pack_storage_sentinel(enc, h_high, h_low)
+    p = sq.params(M, K, 64, bank, topk, h_high=h_high, h_low=h_low)
+    s = 1 - topk / bank
+    assert sq.sq_storage_row_bytes_sentinel(p) * 8 == K * ((1 - s) * h_high + h_low) == want.shape[1] * 8
+    act = sq.Act(p)
+    sq.sq_encode(p, dev(bits), act)
+    packed = Guarded(M * sq.sq_storage_row_bytes_sentinel(p), torch.uint8)
+    sq.sq_pack_storage_sentinel(p, act, packed.t)
+    torch.cuda.synchronize()
+    packed.check()
+    assert np.array_equal(packed.host(np.uint8).reshape(M, -1), want)
+    back = GuardedAct(p)
+    for t in (back.d_lo, back.hi_val, back.mask):
+        t.fill_(0x5A)
+    sq.sq_unpack_storage_sentinel(p, packed.t, back)
+    torch.cuda.synchronize()
+    back.check()
+    assert torch.equal(back.mask, act.mask), "the mask must come back out of the sentinels"
+    assert torch.equal(back.d_lo, act.d_lo) and torch.equal(back.hi_val, act.hi_val)
+    ps = sq.params(M, K, 64, bank, topk, mode=sq.SQ_STATIC, h_high=h_high, h_low=h_low)
+    assert sq.sq_storage_row_bytes_sentinel(ps) == 0
