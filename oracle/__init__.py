@@ -61,6 +61,8 @@ def _load():
         L.sqo_gemm.restype = i32
         L.sqo_static_mask.argtypes = [vp, i64, i32, vp, vp, i64, i32, i32, vp, vp]
         L.sqo_static_mask.restype = i32
+        L.sqo_fma32.argtypes = [i64, vp, vp, vp, vp]
+        L.sqo_fma32.restype = None
         _lib = L
     return _lib
 
@@ -160,6 +162,16 @@ def static_mask(calib_bits: np.ndarray, wq_packed: np.ndarray, w_scale: np.ndarr
     return mask, imp
 
 
+def fma32(a: np.ndarray, b: np.ndarray, c: np.ndarray) -> np.ndarray:
+    """Element-wise fmaf (one rounding), through the C library."""
+    a = np.ascontiguousarray(np.broadcast_to(a, np.broadcast(a, b, c).shape), dtype=np.float32)
+    b = np.ascontiguousarray(np.broadcast_to(b, a.shape), dtype=np.float32)
+    c = np.ascontiguousarray(np.broadcast_to(c, a.shape), dtype=np.float32)
+    out = np.empty_like(a)
+    _load().sqo_fma32(a.size, _p(a), _p(b), _p(c), _p(out))
+    return out
+
+
 def equivalent_bits(h_high: float, h_low: float, s: float) -> float:
     """Equivalent bit width of an SQ-format activation, y = (1-s)*h_high + s*h_low (Section 4.1, Notation)."""
     return (1.0 - s) * h_high + s * h_low
@@ -256,3 +268,26 @@ def unpack_storage_sentinel(packed, K, bank, topk, h_high, h_low, s_lo, s_hi):
 
 def sentinel_row_bytes(K, bank, topk, h_high, h_low):
     return _pairs().sentinel_row_bytes(K, bank, topk, h_high, h_low)
+
+
+# ---- SQ-format on weights at run time (oracle/wsq.py, plain numpy) ----
+_wsq_mod = None
+
+
+def wsq():
+    """oracle.wsq, or -- only for the test that plants mistakes in it -- the copy named by SQ_ORACLE_WSQ_SRC."""
+    global _wsq_mod
+    if _wsq_mod is None:
+        import importlib
+        import importlib.util
+
+        override = os.environ.get("SQ_ORACLE_WSQ_SRC")
+        if override:
+            spec = importlib.util.spec_from_file_location(__name__ + ".wsq_variant", override)
+            mod = importlib.util.module_from_spec(spec)
+            mod.__package__ = __name__
+            spec.loader.exec_module(mod)
+            _wsq_mod = mod
+        else:
+            _wsq_mod = importlib.import_module(__name__ + ".wsq")
+    return _wsq_mod

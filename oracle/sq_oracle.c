@@ -309,3 +309,9 @@ int sqo_static_mask(const uint16_t *calib, int64_t T, int K, const uint8_t *wq, 
   free(imp);
   return SQO_OK;
 }
+
+/* out[i] = fmaf(a[i], b[i], c[i]): the correctly rounded fused multiply-add of the C library, for the numpy
+ * oracles of the layer's variants (numpy has no fused multiply-add). */
+void sqo_fma32(int64_t n, const float *a, const float *b, const float *c, float *out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = fmaf(a[i], b[i], c[i]);
+}
