@@ -233,6 +233,48 @@ int sq_linear(const sq_params *p, const uint16_t *x_bf16, int64_t ldx, const uin
 int sq_linear_noalloc(const sq_params *p, const uint16_t *x_bf16, int64_t ldx, const uint32_t *static_mask,
                       const sq_weight *w, void *y, int64_t ldy, void *stream);
 
+/*
+ * SQ-format on WEIGHTS at run time: the W(SQx)Ay linear layer (Section 3.2.1, Algorithm 1, Figure 1's caption;
+ * Section 3.3; Section 4.1).  Every bank of `bank` input channels of every output channel is a quantisation group:
+ * its `topk` most important weights, I = w^2 / diag(H^-1)^2, are h_high-bit codes with one scale, the others
+ * h_low-bit codes with another; the low part keeps its shape and carries v_mask = -2^(h_low-1) at the high
+ * positions, the high part is compact (ascending channel order).  The activations are plain per-token symmetric
+ * INT8 or INT4 codes.  Per bank g the two integer products are exact; they are dequantised and added bank by bank:
+ *     f = 0;  for g:  t = fl(float(acc_lo_g) * s_lo[n,g]);  t = fma(float(acc_hi_g), s_hi[n,g], t);  f = fl(f + t)
+ *     Y[m,n] = fl(f * s_a[m])
+ * `p`: M, K, N, bank (64 or 128), topk (1 ... bank), h_high / h_low (a pair as above), out_dtype; mode is not read.
+ * These kernels are a first, untuned form (the per-bank scales make the layer bound by vector arithmetic).
+ */
+typedef struct {
+  uint8_t *lo;      /* [N, K/2]  low codes in 4-bit containers (sign-extended), v_mask at the high positions */
+  int8_t *hi_val;   /* [N, K/bank, topk] */
+  float *scale_lo;  /* [N, K/bank] */
+  float *scale_hi;  /* [N, K/bank] */
+} sq_wsq;
+
+/* Byte sizes of the arrays of an sq_wsq (scale: each of the two); returns the total, 0 for invalid parameters. */
+size_t sq_wsq_bytes(const sq_params *p, size_t *lo, size_t *hi_val, size_t *scale);
+/* Offline: w_bf16 device [N, ldw] (ldw >= K) -> SQ-format.  hinv_diag: device [K] positive floats, diag(H^-1) of
+ * Algorithm 1, or NULL for 1 (ranking by |w|); ties in importance go to the lower channel. */
+int sq_wsq_encode(const sq_params *p, const uint16_t *w_bf16, int64_t ldw, const float *hinv_diag, const sq_wsq *out,
+                  void *stream);
+/* Offline: the compute-ready image of the weights, N*K/2 + N*K bytes (low part with zeros at the high positions,
+ * then the high part as a zero-padded INT8 matrix in the byte order of sq_act::hi_dense). */
+size_t sq_wsq_prepack_bytes(const sq_params *p);
+int sq_wsq_prepack(const sq_params *p, const sq_wsq *w, void *out, void *stream);
+/* Plain per-token symmetric quantisation of X [M, ldx] (bf16) to `bits` = 8 or 4: a8 device [M, K] codes (stored per 8
+ * channels as even channels, then odd channels: the byte order of the weight images), a_scale device [M]. */
+int sq_quantize_act(const sq_params *p, const uint16_t *x_bf16, int64_t ldx, int bits, int8_t *a8, float *a_scale,
+                    void *stream);
+/* The layer's products and fp32 accumulation.  prepacked: output of sq_wsq_prepack.  y device [M, ldy].
+ * acc_lo_dbg / acc_hi_dbg: optional device [M, N, K/bank] int32, the exact per-bank products. */
+int sq_wsq_gemm(const sq_params *p, const int8_t *a8, const float *a_scale, const sq_wsq *w, const void *prepacked, void *y,
+                int64_t ldy, int32_t *acc_lo_dbg, int32_t *acc_hi_dbg, void *stream);
+/* sq_quantize_act into the workspace followed by sq_wsq_gemm. */
+size_t sq_wsq_linear_workspace_bytes(const sq_params *p);
+int sq_wsq_linear(const sq_params *p, const uint16_t *x_bf16, int64_t ldx, int act_bits, const sq_wsq *w,
+                  const void *prepacked, void *y, int64_t ldy, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Reference point for the benchmark: a plain per-token W4A8 layer (no SQ split) on the same
  * INT8 matrix-core kernel, which is what Section 4.2 says W4A8 falls back to on GPUs.
  * sq_dense_w4a8_prepack reorders the nibbles of wq [N, K/2] into `out` (N*K/2 bytes) for it; the

@@ -25,6 +25,8 @@ EXPORTS = (
     "sq_init", "sq_gemm_variant", "sq_linear_noalloc", "sq_lo_compact_bytes",
     "sq_storage_row_bytes", "sq_pack_storage", "sq_unpack_storage", "sq_probe_mfma_alt", "sq_probe_fp6_tile",
     "sq_storage_row_bytes_sentinel", "sq_pack_storage_sentinel", "sq_unpack_storage_sentinel",
+    "sq_wsq_bytes", "sq_wsq_encode", "sq_wsq_prepack_bytes", "sq_wsq_prepack", "sq_quantize_act", "sq_wsq_gemm",
+    "sq_wsq_linear_workspace_bytes", "sq_wsq_linear",
 )
 SQ_NOALLOC_SCRATCH_BYTES = 8 << 20
 
@@ -45,6 +47,11 @@ class sq_act(ctypes.Structure):
     _fields_ = [("d_lo", ctypes.c_void_p), ("hi_val", ctypes.c_void_p), ("mask", ctypes.c_void_p),
                 ("scale_lo", ctypes.c_void_p), ("scale_hi", ctypes.c_void_p), ("hi_dense", ctypes.c_void_p),
                 ("lo_compact", ctypes.c_void_p)]
+
+
+class sq_wsq(ctypes.Structure):
+    _fields_ = [("lo", ctypes.c_void_p), ("hi_val", ctypes.c_void_p), ("scale_lo", ctypes.c_void_p),
+                ("scale_hi", ctypes.c_void_p)]
 
 
 class sq_weight(ctypes.Structure):
@@ -103,6 +110,19 @@ def lib() -> ctypes.CDLL:
         L.sq_unpack_storage_sentinel.restype = ctypes.c_int
         L.sq_pack_storage.restype = ctypes.c_int
         L.sq_unpack_storage.restype = ctypes.c_int
+        L.sq_wsq_bytes.argtypes = [P(sq_params), P(sz), P(sz), P(sz)]
+        L.sq_wsq_bytes.restype = sz
+        L.sq_wsq_encode.argtypes = [P(sq_params), vp, i64, vp, P(sq_wsq), vp]
+        L.sq_wsq_prepack_bytes.argtypes = [P(sq_params)]
+        L.sq_wsq_prepack_bytes.restype = sz
+        L.sq_wsq_prepack.argtypes = [P(sq_params), P(sq_wsq), vp, vp]
+        L.sq_quantize_act.argtypes = [P(sq_params), vp, i64, ctypes.c_int, vp, vp, vp]
+        L.sq_wsq_gemm.argtypes = [P(sq_params), vp, vp, P(sq_wsq), vp, vp, i64, vp, vp, vp]
+        L.sq_wsq_linear_workspace_bytes.argtypes = [P(sq_params)]
+        L.sq_wsq_linear_workspace_bytes.restype = sz
+        L.sq_wsq_linear.argtypes = [P(sq_params), vp, i64, ctypes.c_int, P(sq_wsq), vp, vp, i64, vp, sz, vp]
+        for f in (L.sq_wsq_encode, L.sq_wsq_prepack, L.sq_quantize_act, L.sq_wsq_gemm, L.sq_wsq_linear):
+            f.restype = ctypes.c_int
         L.sq_init.argtypes = []
         L.sq_init.restype = ctypes.c_int
         L.sq_gemm_variant.argtypes = [P(sq_params)]
@@ -287,6 +307,65 @@ def sq_unpack_storage_sentinel(p: sq_params, packed, a: Act, stream=None) -> Non
     ac = a.c()
     _check(lib().sq_unpack_storage_sentinel(ctypes.byref(p), _ptr(packed), ctypes.byref(ac), _stream(stream)),
            "sq_unpack_storage_sentinel")
+
+
+class WeightSQ:
+    """Device buffers of a weight matrix in SQ-format (torch tensors)."""
+
+    def __init__(self, p: sq_params, device="cuda"):
+        import torch
+
+        a, b, c = (ctypes.c_size_t() for _ in range(3))
+        tot = lib().sq_wsq_bytes(ctypes.byref(p), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+        if tot == 0:
+            raise SqError(-3, "sq_wsq_bytes (invalid parameters)")
+        self.p = p
+        self.lo = torch.empty(a.value, dtype=torch.uint8, device=device)
+        self.hi_val = torch.empty(b.value, dtype=torch.int8, device=device)
+        self.scale_lo = torch.empty(c.value // 4, dtype=torch.float32, device=device)
+        self.scale_hi = torch.empty(c.value // 4, dtype=torch.float32, device=device)
+
+    def c(self) -> sq_wsq:
+        return sq_wsq(_ptr(self.lo), _ptr(self.hi_val), _ptr(self.scale_lo), _ptr(self.scale_hi))
+
+
+def sq_wsq_encode(p: sq_params, w_bf16, out: WeightSQ, hinv_diag=None, ldw: Optional[int] = None, stream=None) -> None:
+    oc = out.c()
+    _check(lib().sq_wsq_encode(ctypes.byref(p), _ptr(w_bf16), p.K if ldw is None else ldw, _ptr(hinv_diag), ctypes.byref(oc),
+                               _stream(stream)), "sq_wsq_encode")
+
+
+def sq_wsq_prepack_bytes(p: sq_params) -> int:
+    return int(lib().sq_wsq_prepack_bytes(ctypes.byref(p)))
+
+
+def sq_wsq_prepack(p: sq_params, w: WeightSQ, out, stream=None) -> None:
+    wc = w.c()
+    _check(lib().sq_wsq_prepack(ctypes.byref(p), ctypes.byref(wc), _ptr(out), _stream(stream)), "sq_wsq_prepack")
+
+
+def sq_quantize_act(p: sq_params, x_bf16, a8, a_scale, bits: int = 8, ldx: Optional[int] = None, stream=None) -> None:
+    _check(lib().sq_quantize_act(ctypes.byref(p), _ptr(x_bf16), p.K if ldx is None else ldx, int(bits), _ptr(a8),
+                                 _ptr(a_scale), _stream(stream)), "sq_quantize_act")
+
+
+def sq_wsq_gemm(p: sq_params, a8, a_scale, w: WeightSQ, prepacked, y, acc_lo_dbg=None, acc_hi_dbg=None,
+                ldy: Optional[int] = None, stream=None) -> None:
+    wc = w.c()
+    _check(lib().sq_wsq_gemm(ctypes.byref(p), _ptr(a8), _ptr(a_scale), ctypes.byref(wc), _ptr(prepacked), _ptr(y),
+                             p.N if ldy is None else ldy, _ptr(acc_lo_dbg), _ptr(acc_hi_dbg), _stream(stream)), "sq_wsq_gemm")
+
+
+def sq_wsq_linear_workspace_bytes(p: sq_params) -> int:
+    return int(lib().sq_wsq_linear_workspace_bytes(ctypes.byref(p)))
+
+
+def sq_wsq_linear(p: sq_params, x_bf16, w: WeightSQ, prepacked, y, workspace, act_bits: int = 8, ldx: Optional[int] = None,
+                  ldy: Optional[int] = None, stream=None) -> None:
+    wc = w.c()
+    _check(lib().sq_wsq_linear(ctypes.byref(p), _ptr(x_bf16), p.K if ldx is None else ldx, int(act_bits), ctypes.byref(wc),
+                               _ptr(prepacked), _ptr(y), p.N if ldy is None else ldy, _ptr(workspace),
+                               workspace.numel() * workspace.element_size(), _stream(stream)), "sq_wsq_linear")
 
 
 def sq_dense_w4a8_prepack(p: sq_params, wq, out, stream=None) -> None:

@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libsq.so")
 
-SOURCES = ["sq_encode.hip", "sq_encode_dyn.hip", "sq_encode_static.hip", "sq_storage.hip", "sq_gemm.hip", "sq_probe.hip", "sq_calib.hip", "sq_noalloc.hip", "sq_api.cpp"]
+SOURCES = ["sq_encode.hip", "sq_encode_dyn.hip", "sq_encode_static.hip", "sq_storage.hip", "sq_wsq.hip", "sq_gemm.hip", "sq_probe.hip", "sq_calib.hip", "sq_noalloc.hip", "sq_api.cpp"]
 
 # -ffp-contract=off: the encoder's multiply-then-round and the epilogue's multiply / fma / multiply
 # must stay the separate fp32 operations the layer is defined with.

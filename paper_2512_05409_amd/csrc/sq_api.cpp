@@ -374,6 +374,108 @@ int sq_unpack_storage_sentinel(const sq_params* p, const uint8_t* packed, const 
   return storage_call(p, a, const_cast<uint8_t*>(packed), false, true, stream);
 }
 
+// ---- SQ-format on weights ----
+static int check_wsq_params(const sq_params* p) {
+  if (!p) return SQ_ERR_NULL;
+  if (p->M <= 0 || p->K <= 0 || p->N <= 0) return SQ_ERR_SHAPE;
+  if (p->bank != 64 && p->bank != 128) return SQ_ERR_UNSUPPORTED;
+  if (p->K % p->bank || p->K > 131072 || p->M > (1 << 22) || p->N > (1 << 24)) return SQ_ERR_SHAPE;
+  if (p->topk < 1 || p->topk > p->bank) return SQ_ERR_UNSUPPORTED;
+  if (p->out_dtype != SQ_OUT_F32 && p->out_dtype != SQ_OUT_BF16) return SQ_ERR_UNSUPPORTED;
+  const int hh = p->h_high ? p->h_high : 8, hl = p->h_low ? p->h_low : 4;
+  if (!((hh == 8 && (hl == 4 || hl == 3 || hl == 2)) || (hh == 4 && hl == 2))) return SQ_ERR_UNSUPPORTED;
+  return SQ_OK;
+}
+
+static int check_wsq(const sq_wsq* w) {
+  if (!w || !w->lo || !w->hi_val || !w->scale_lo || !w->scale_hi) return SQ_ERR_NULL;
+  if (!aligned16(w->lo) || !aligned16(w->hi_val) || !aligned16(w->scale_lo) || !aligned16(w->scale_hi)) return SQ_ERR_ALIGN;
+  return SQ_OK;
+}
+
+size_t sq_wsq_bytes(const sq_params* p, size_t* lo, size_t* hi_val, size_t* scale) {
+  if (check_wsq_params(p) != SQ_OK) return 0;
+  const size_t G = p->K / p->bank;
+  const size_t l = static_cast<size_t>(p->N) * (p->K / 2), h = static_cast<size_t>(p->N) * G * p->topk, s = static_cast<size_t>(p->N) * G * 4;
+  if (lo) *lo = l;
+  if (hi_val) *hi_val = h;
+  if (scale) *scale = s;
+  return l + h + 2 * s;
+}
+
+int sq_wsq_encode(const sq_params* p, const uint16_t* w_bf16, int64_t ldw, const float* hinv_diag, const sq_wsq* out,
+                  void* stream) {
+  int rc = check_wsq_params(p);
+  if (rc != SQ_OK) return rc;
+  if (!w_bf16) return SQ_ERR_NULL;
+  if ((rc = check_wsq(out)) != SQ_OK) return rc;
+  if (ldw < p->K) return SQ_ERR_SHAPE;
+  if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
+  return sq::launch_wsq_encode(*p, w_bf16, ldw, hinv_diag, *out, static_cast<hipStream_t>(stream));
+}
+
+size_t sq_wsq_prepack_bytes(const sq_params* p) {
+  if (check_wsq_params(p) != SQ_OK) return 0;
+  return static_cast<size_t>(p->N) * (p->K / 2) + static_cast<size_t>(p->N) * p->K;
+}
+
+int sq_wsq_prepack(const sq_params* p, const sq_wsq* w, void* out, void* stream) {
+  int rc = check_wsq_params(p);
+  if (rc != SQ_OK) return rc;
+  if ((rc = check_wsq(w)) != SQ_OK) return rc;
+  if (!out) return SQ_ERR_NULL;
+  if (!aligned16(out)) return SQ_ERR_ALIGN;
+  if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
+  uint8_t* o = static_cast<uint8_t*>(out);
+  return sq::launch_wsq_prepack(*p, *w, o, reinterpret_cast<int8_t*>(o + static_cast<size_t>(p->N) * (p->K / 2)),
+                                static_cast<hipStream_t>(stream));
+}
+
+int sq_quantize_act(const sq_params* p, const uint16_t* x_bf16, int64_t ldx, int bits, int8_t* a8, float* a_scale,
+                    void* stream) {
+  if (!p || !x_bf16 || !a8 || !a_scale) return SQ_ERR_NULL;
+  if (p->M <= 0 || p->K <= 0 || p->K % 64 || p->K > 131072 || ldx < p->K) return SQ_ERR_SHAPE;
+  if (bits != 8 && bits != 4) return SQ_ERR_UNSUPPORTED;
+  if (!aligned16(x_bf16) || (ldx % 8) || !aligned16(a8)) return SQ_ERR_ALIGN;
+  int rc = sq::ensure_device_ready();
+  if (rc != SQ_OK) return rc;
+  return sq::launch_quantize_act(*p, x_bf16, ldx, bits, a8, a_scale, static_cast<hipStream_t>(stream));
+}
+
+int sq_wsq_gemm(const sq_params* p, const int8_t* a8, const float* a_scale, const sq_wsq* w, const void* prepacked, void* y,
+                int64_t ldy, int32_t* acc_lo_dbg, int32_t* acc_hi_dbg, void* stream) {
+  int rc = check_wsq_params(p);
+  if (rc != SQ_OK) return rc;
+  if (!a8 || !a_scale || !prepacked) return SQ_ERR_NULL;
+  if ((rc = check_wsq(w)) != SQ_OK) return rc;
+  if ((rc = check_y(p, y, ldy)) != SQ_OK) return rc;
+  if (!aligned16(a8) || !aligned16(prepacked)) return SQ_ERR_ALIGN;
+  if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
+  const uint8_t* o = static_cast<const uint8_t*>(prepacked);
+  return sq::launch_wsq_gemm(*p, a8, a_scale, *w, o, reinterpret_cast<const int8_t*>(o + static_cast<size_t>(p->N) * (p->K / 2)),
+                             y, ldy, acc_lo_dbg, acc_hi_dbg, static_cast<hipStream_t>(stream));
+}
+
+size_t sq_wsq_linear_workspace_bytes(const sq_params* p) {
+  if (check_wsq_params(p) != SQ_OK) return 0;
+  return align_up(static_cast<size_t>(p->M) * p->K, 256) + align_up(static_cast<size_t>(p->M) * 4, 256);
+}
+
+int sq_wsq_linear(const sq_params* p, const uint16_t* x_bf16, int64_t ldx, int act_bits, const sq_wsq* w,
+                  const void* prepacked, void* y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_wsq_params(p);
+  if (rc != SQ_OK) return rc;
+  if (!workspace || workspace_bytes < sq_wsq_linear_workspace_bytes(p)) return SQ_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SQ_ERR_ALIGN;
+  if ((rc = check_wsq(w)) != SQ_OK) return rc;
+  if (!prepacked) return SQ_ERR_NULL;
+  if ((rc = check_y(p, y, ldy)) != SQ_OK) return rc;
+  int8_t* a8 = static_cast<int8_t*>(workspace);
+  float* sa = reinterpret_cast<float*>(static_cast<char*>(workspace) + align_up(static_cast<size_t>(p->M) * p->K, 256));
+  if ((rc = sq_quantize_act(p, x_bf16, ldx, act_bits, a8, sa, stream)) != SQ_OK) return rc;
+  return sq_wsq_gemm(p, a8, sa, w, prepacked, y, ldy, nullptr, nullptr, stream);
+}
+
 int sq_dense_w4a8_prepack(const sq_params* p, const uint8_t* wq, void* out, void* stream) {
   if (!p || !wq || !out) return SQ_ERR_NULL;
   if (p->K <= 0 || p->N <= 0 || p->K % 64 || p->K > 131072) return SQ_ERR_SHAPE;
