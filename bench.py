@@ -58,6 +58,7 @@ def parse():
     ap.add_argument("--no-dense-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="also replay the steps from a captured HIP graph (launch overhead removed; matters for few-token shapes)")
+    ap.add_argument("--weights-sq", action="store_true", help="also time the SQ-format-on-weights layer (sq_wsq_linear) of the same shape")
     ap.add_argument("--no-probes", action="store_true", help="skip the measured matrix-instruction and streaming rates")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the CPU-oracle sample (0: sized for about 20 s)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -431,6 +432,31 @@ def main():
                                      "kernel": sq.sq_gemm_variant(pt),
                                      "note": "sq_linear in mode SQ_DYNAMIC_TIED (encode + one INT8 x INT4 product): "
                                              "MACs issued = M*N*K; not the layer the headline value is quoted on"}
+
+    if args.weights_sq and not hbm_bound:
+        # The second workload of the paper, SQ-format on WEIGHTS (W(SQ)A8): the same shape with the weights encoded per
+        # (output channel, bank) group (offline, not timed) and plain per-token INT8 activations.
+        pw = sq.params(M, K, N, 64 if b < 64 else b, k if b >= 64 else 8, out_dtype=sq.SQ_OUT_BF16)
+        w_bf16 = (torch.randn(N, K, device="cuda") * 0.04).to(torch.bfloat16).view(torch.int16)
+        wsq = sq.WeightSQ(pw)
+        sq.sq_wsq_encode(pw, w_bf16, wsq)
+        prew = torch.empty(sq.sq_wsq_prepack_bytes(pw), dtype=torch.uint8, device="cuda")
+        sq.sq_wsq_prepack(pw, wsq, prew)
+        wsw = torch.empty(sq.sq_wsq_linear_workspace_bytes(pw), dtype=torch.uint8, device="cuda")
+        for i in range(3):
+            sq.sq_wsq_linear(pw, xs[i % n_x], wsq, prew, ys[i % n_y], wsw)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(5, args.steps // 4)
+        e0.record()
+        for i in range(reps):
+            sq.sq_wsq_linear(pw, xs[i % n_x], wsq, prew, ys[i % n_y], wsw)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        out["weights_sq_variant"] = {"ms_per_step": ms, "tops_2MNK": ops_eff / (ms * 1e-3) / 1e12, "bank": pw.bank, "topk": pw.topk,
+                                     "note": "sq_wsq_linear: per-token INT8 activations x SQ-format weights with per-(channel, bank) "
+                                             "scales; bound by the per-bank fp32 fold (vector arithmetic), not by the matrix cores"}
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_rows)

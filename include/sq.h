@@ -243,7 +243,9 @@ int sq_linear_noalloc(const sq_params *p, const uint16_t *x_bf16, int64_t ldx, c
  *     f = 0;  for g:  t = fl(float(acc_lo_g) * s_lo[n,g]);  t = fma(float(acc_hi_g), s_hi[n,g], t);  f = fl(f + t)
  *     Y[m,n] = fl(f * s_a[m])
  * `p`: M, K, N, bank (64 or 128), topk (1 ... bank), h_high / h_low (a pair as above), out_dtype; mode is not read.
- * These kernels are a first, untuned form (the per-bank scales make the layer bound by vector arithmetic).
+ * Per-group low scales below 2^-122 are outside the supported range (the compute image stores them divided by 16).
+ * The per-bank scales make the layer bound by vector arithmetic (five instructions per accumulator register and
+ * bank), not by the matrix cores.
  */
 typedef struct {
   uint8_t *lo;      /* [N, K/2]  low codes in 4-bit containers (sign-extended), v_mask at the high positions */
@@ -258,8 +260,9 @@ size_t sq_wsq_bytes(const sq_params *p, size_t *lo, size_t *hi_val, size_t *scal
  * Algorithm 1, or NULL for 1 (ranking by |w|); ties in importance go to the lower channel. */
 int sq_wsq_encode(const sq_params *p, const uint16_t *w_bf16, int64_t ldw, const float *hinv_diag, const sq_wsq *out,
                   void *stream);
-/* Offline: the compute-ready image of the weights, N*K/2 + N*K bytes (low part with zeros at the high positions,
- * then the high part as a zero-padded INT8 matrix in the byte order of sq_act::hi_dense). */
+/* Offline: the compute-ready image of the weights, sq_wsq_prepack_bytes(p) bytes (low part with zeros at the high
+ * positions; the high part as a zero-padded INT8 matrix in the byte order of sq_act::hi_dense; the two scale arrays
+ * transposed to [K/bank, N rounded up to 128]). */
 size_t sq_wsq_prepack_bytes(const sq_params *p);
 int sq_wsq_prepack(const sq_params *p, const sq_wsq *w, void *out, void *stream);
 /* Plain per-token symmetric quantisation of X [M, ldx] (bf16) to `bits` = 8 or 4: a8 device [M, K] codes (stored per 8

@@ -33,6 +33,7 @@ int ensure_device_ready() {
   int rc = init_gemm_kernels();
   if (rc == SQ_OK) rc = init_encode_kernels();
   if (rc == SQ_OK) rc = init_scratch(dev);
+  if (rc == SQ_OK) rc = init_wsq_kernels();
   if (rc == SQ_OK) ready[dev].store(1, std::memory_order_release);
   return rc;
 }
@@ -414,9 +415,13 @@ int sq_wsq_encode(const sq_params* p, const uint16_t* w_bf16, int64_t ldw, const
   return sq::launch_wsq_encode(*p, w_bf16, ldw, hinv_diag, *out, static_cast<hipStream_t>(stream));
 }
 
+static size_t wsq_scales_t_bytes(const sq_params* p) {  // one transposed, padded scale array
+  return static_cast<size_t>(p->K / p->bank) * ((p->N + 127) / 128 * 128) * 4;
+}
+
 size_t sq_wsq_prepack_bytes(const sq_params* p) {
   if (check_wsq_params(p) != SQ_OK) return 0;
-  return static_cast<size_t>(p->N) * (p->K / 2) + static_cast<size_t>(p->N) * p->K;
+  return static_cast<size_t>(p->N) * (p->K / 2) + static_cast<size_t>(p->N) * p->K + 2 * wsq_scales_t_bytes(p);
 }
 
 int sq_wsq_prepack(const sq_params* p, const sq_wsq* w, void* out, void* stream) {
@@ -427,8 +432,10 @@ int sq_wsq_prepack(const sq_params* p, const sq_wsq* w, void* out, void* stream)
   if (!aligned16(out)) return SQ_ERR_ALIGN;
   if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
   uint8_t* o = static_cast<uint8_t*>(out);
-  return sq::launch_wsq_prepack(*p, *w, o, reinterpret_cast<int8_t*>(o + static_cast<size_t>(p->N) * (p->K / 2)),
-                                static_cast<hipStream_t>(stream));
+  uint8_t* hd = o + static_cast<size_t>(p->N) * (p->K / 2);
+  uint8_t* sl = hd + static_cast<size_t>(p->N) * p->K;
+  return sq::launch_wsq_prepack(*p, *w, o, reinterpret_cast<int8_t*>(hd), reinterpret_cast<float*>(sl),
+                                reinterpret_cast<float*>(sl + wsq_scales_t_bytes(p)), static_cast<hipStream_t>(stream));
 }
 
 int sq_quantize_act(const sq_params* p, const uint16_t* x_bf16, int64_t ldx, int bits, int8_t* a8, float* a_scale,
@@ -452,8 +459,11 @@ int sq_wsq_gemm(const sq_params* p, const int8_t* a8, const float* a_scale, cons
   if (!aligned16(a8) || !aligned16(prepacked)) return SQ_ERR_ALIGN;
   if ((rc = sq::ensure_device_ready()) != SQ_OK) return rc;
   const uint8_t* o = static_cast<const uint8_t*>(prepacked);
-  return sq::launch_wsq_gemm(*p, a8, a_scale, *w, o, reinterpret_cast<const int8_t*>(o + static_cast<size_t>(p->N) * (p->K / 2)),
-                             y, ldy, acc_lo_dbg, acc_hi_dbg, static_cast<hipStream_t>(stream));
+  const uint8_t* hd = o + static_cast<size_t>(p->N) * (p->K / 2);
+  const uint8_t* sl = hd + static_cast<size_t>(p->N) * p->K;
+  return sq::launch_wsq_gemm(*p, a8, a_scale, *w, o, reinterpret_cast<const int8_t*>(hd), reinterpret_cast<const float*>(sl),
+                             reinterpret_cast<const float*>(sl + wsq_scales_t_bytes(p)), y, ldy, acc_lo_dbg, acc_hi_dbg,
+                             static_cast<hipStream_t>(stream));
 }
 
 size_t sq_wsq_linear_workspace_bytes(const sq_params* p) {

@@ -63,10 +63,13 @@ int launch_storage(const sq_params& p, const sq_act& act, uint8_t* packed, bool 
 
 // SQ-format on weights (sq_wsq.hip).
 int launch_wsq_encode(const sq_params& p, const uint16_t* w, int64_t ldw, const float* hinv, const sq_wsq& out, hipStream_t st);
-int launch_wsq_prepack(const sq_params& p, const sq_wsq& w, uint8_t* lo_clean, int8_t* hi_dense, hipStream_t st);
+int init_wsq_kernels();
+int launch_wsq_prepack(const sq_params& p, const sq_wsq& w, uint8_t* lo_clean, int8_t* hi_dense, float* s_lo_t, float* s_hi_t,
+                       hipStream_t st);
 int launch_quantize_act(const sq_params& p, const uint16_t* x, int64_t ldx, int bits, int8_t* a8, float* a_scale, hipStream_t st);
 int launch_wsq_gemm(const sq_params& p, const int8_t* a8, const float* a_scale, const sq_wsq& w, const uint8_t* lo_clean,
-                    const int8_t* hi_dense, void* y, int64_t ldy, int32_t* acc_lo_dbg, int32_t* acc_hi_dbg, hipStream_t st);
+                    const int8_t* hi_dense, const float* s_lo_t, const float* s_hi_t, void* y, int64_t ldy,
+                    int32_t* acc_lo_dbg, int32_t* acc_hi_dbg, hipStream_t st);
 
 struct GemmArgs {
   int M, N, K;          // K of the layer

@@ -270,7 +270,200 @@ __global__ __launch_bounds__(256) void wsq_gemm_kernel(WsqGemmArgs g) {
   }
 }
 
+// ---- the throughput kernel ----
+// 128 tokens x 128 output channels per workgroup, four waves of 64 x 64 (2 x 2 tiles of 32 x 32: 64 fp32 and 128
+// integer accumulator registers per lane).  A K step is 64 channels; its operands (8 KB of activation codes, 8 KB of
+// INT8 high weights, 4 KB of packed low weights, 1 KB of the bank's scales) are copied into one of three LDS stages
+// by LDS-direct loads two steps ahead, rows XOR-swizzled as in the activation-SQ kernel.  After the last step of a
+// bank the two integer tiles are folded into the fp32 accumulators (5 vector instructions per register): that fold,
+// not the matrix instructions, is what bounds the kernel; with two workgroups per compute unit one wave's fold
+// overlaps the other's matrix instructions.
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+constexpr int W2_A = 0, W2_WH = 8192, W2_WL = 16384, W2_SC = 20480, W2_STAGE = 21504, W2_NS = 3;
+
+__device__ __forceinline__ int w2_off4(int row, int c) { return (row << 6) + (((c ^ (row >> 2)) & 3) << 4); }  // 64-byte rows
+__device__ __forceinline__ int w2_off2(int row, int c) { return (row << 5) + (((c ^ (row >> 3)) & 1) << 4); }  // 32-byte rows
+
+template <int N>
+__device__ __forceinline__ void w2_wait() {  // at most N vector-memory operations outstanding, LDS reads drained, barrier
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (0 << 8) | ((N >> 4) << 14));
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+struct Wsq2Args {
+  int M, N, K, G, Npad, bpb;  // bpb: 64-channel steps per bank (1 or 2)
+  const int8_t* a8;
+  const float* a_scale;
+  const uint8_t* lo_clean;
+  const int8_t* hi_dense;
+  const float* s_lo_t;  // [G, Npad]
+  const float* s_hi_t;
+  void* y;
+  int64_t ldy;
+  int out_bf16;
+};
+
+__global__ __launch_bounds__(256, 2) void wsq_gemm2_kernel(Wsq2Args g) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int r = lane & 31, h = lane >> 5;
+  const int m0 = blockIdx.y * 128, n0 = blockIdx.x * 128;
+  const int steps = g.K / 64;
+
+  // per-lane sources of the copies of one step (at k = 0)
+  const char* pa[2];
+  const char* pwh[2];
+  const char* pwl;
+  for (int i = 0; i < 2; ++i) {
+    const int idx = tid + 256 * i, row = idx >> 2, c = ((idx & 3) ^ (row >> 2)) & 3;
+    pa[i] = reinterpret_cast<const char*>(g.a8) + static_cast<int64_t>(min(m0 + row, g.M - 1)) * g.K + c * 16;
+    pwh[i] = reinterpret_cast<const char*>(g.hi_dense) + static_cast<int64_t>(min(n0 + row, g.N - 1)) * g.K + c * 16;
+  }
+  {
+    const int row = tid >> 1, c = ((tid & 1) ^ (row >> 3)) & 1;
+    pwl = reinterpret_cast<const char*>(g.lo_clean) + static_cast<int64_t>(min(n0 + row, g.N - 1)) * (g.K / 2) + c * 16;
+  }
+  // scales of a bank for the workgroup's 128 channels: lanes 0-31 of wave 0 the low ones, lanes 32-63 the high ones
+  const char* psc = reinterpret_cast<const char*>(lane < 32 ? g.s_lo_t : g.s_hi_t) + (static_cast<int64_t>(n0) + (lane & 31) * 4) * 4;
+
+  auto issue = [&](int step) {
+    char* st = lds + (step % W2_NS) * W2_STAGE;
+    for (int i = 0; i < 2; ++i) {
+      const char* src = pa[i] + step * 64;
+      __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(st + W2_A + (256 * i + 64 * wave) * 16), 16, 0, 0);
+    }
+    for (int i = 0; i < 2; ++i) {
+      const char* src = pwh[i] + step * 64;
+      __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(st + W2_WH + (256 * i + 64 * wave) * 16), 16, 0, 0);
+    }
+    {
+      const char* src = pwl + step * 32;
+      __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(st + W2_WL + 64 * wave * 16), 16, 0, 0);
+    }
+    if (wave == 0) {
+      const char* src = psc + static_cast<int64_t>(step / g.bpb) * g.Npad * 4;
+      __builtin_amdgcn_global_load_lds(src, (lds_ptr_t)(st + W2_SC), 16, 0, 0);
+    }
+  };
+
+  issue(0);
+  if (steps > 1) issue(1);
+
+  float f[2][2][16];
+  v16i acc_lo[2][2], acc_hi[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) f[i][j][q] = 0.0f;
+  const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+  for (int kt = 0; kt < steps; ++kt) {
+    // step kt has landed when at most the copies of step kt+1 are outstanding (wave 0 issues one more per step)
+    if (kt + 1 < steps) {
+      if (wave == 0) w2_wait<6>();
+      else w2_wait<5>();
+    } else {
+      w2_wait<0>();
+    }
+    // the stage of step kt-1 is free now (every wave has passed its fold / its last read of it before this barrier)
+    if (kt + 2 < steps) issue(kt + 2);
+    const char* st = lds + (kt % W2_NS) * W2_STAGE;
+    v4i a[2][2], wh[2][2];
+    v4u wl[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) a[i][s2] = *reinterpret_cast<const v4i*>(st + W2_A + w2_off4(64 * wm + 32 * i + r, 2 * h + s2));
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) wh[j][s2] = *reinterpret_cast<const v4i*>(st + W2_WH + w2_off4(64 * wn + 32 * j + r, 2 * h + s2));
+      wl[j] = *reinterpret_cast<const v4u*>(st + W2_WL + w2_off2(64 * wn + 32 * j + r, h));
+    }
+    const bool first = kt % g.bpb == 0;  // first step of a bank: its products start from zero (no registers to clear)
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const v4i wlo = widen_half(wl[j], s2);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          if (s2 == 0 && first) {
+            acc_lo[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i][s2], wlo, zero, 0, 0, 0);
+            acc_hi[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i][s2], wh[j][s2], zero, 0, 0, 0);
+          } else {
+            acc_lo[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i][s2], wlo, acc_lo[i][j], 0, 0, 0);
+            acc_hi[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i][s2], wh[j][s2], acc_hi[i][j], 0, 0, 0);
+          }
+        }
+      }
+    if ((kt + 1) % g.bpb == 0) {  // last step of a bank: fold its two integer tiles into the fp32 accumulators
+      const float* sc = reinterpret_cast<const float*>(st + W2_SC);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const float sl = sc[64 * wn + 32 * j + r], sh = sc[128 + 64 * wn + 32 * j + r];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int q = 0; q < 16; ++q) {
+            // the widened low weights carry a factor 16, which the transposed low scales carry inverted (sl is
+            // s_lo / 16: float(16 a) * (s / 16) is float(a) * s bit for bit while s / 16 is a normal number)
+            float t = __fmul_rn(static_cast<float>(acc_lo[i][j][q]), sl);
+            t = __fmaf_rn(static_cast<float>(acc_hi[i][j][q]), sh, t);
+            f[i][j][q] = __fadd_rn(f[i][j][q], t);
+          }
+      }
+    }
+  }
+
+  // ---- epilogue: y = f * s_a[m] ----
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int m = m0 + 64 * wm + 32 * i + 8 * (q >> 2) + 4 * h + (q & 3);
+      if (m < g.M) {
+        const float sa = g.a_scale[m];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int n = n0 + 64 * wn + 32 * j + r;
+          if (n < g.N) {
+            const float y = __fmul_rn(f[i][j][q], sa);
+            const int64_t o = static_cast<int64_t>(m) * g.ldy + n;
+            if (g.out_bf16) reinterpret_cast<uint16_t*>(g.y)[o] = f32_to_bf16_rne(y);
+            else reinterpret_cast<float*>(g.y)[o] = y;
+          }
+        }
+      }
+    }
+}
+
+// scales [N, G] -> [G, Npad] (zero beyond N), so that a bank's scales of 128 consecutive channels are contiguous;
+// the low scales are stored divided by 16 (exact for every scale above 2^-122)
+__global__ __launch_bounds__(256) void wsq_scales_t_kernel(int N, int G, int Npad, const float* __restrict__ s_lo,
+                                                           const float* __restrict__ s_hi, float* __restrict__ lo_t,
+                                                           float* __restrict__ hi_t) {
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (idx >= static_cast<int64_t>(G) * Npad) return;
+  const int gq = static_cast<int>(idx / Npad), n = static_cast<int>(idx - static_cast<int64_t>(gq) * Npad);
+  lo_t[idx] = n < N ? s_lo[static_cast<int64_t>(n) * G + gq] * 0.0625f : 0.0f;  // / 16: see the fold of wsq_gemm2_kernel
+  hi_t[idx] = n < N ? s_hi[static_cast<int64_t>(n) * G + gq] : 0.0f;
+}
+
 }  // namespace
+
+int init_wsq_kernels() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(wsq_gemm2_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             W2_NS * W2_STAGE) == hipSuccess
+             ? SQ_OK
+             : SQ_ERR_LAUNCH;
+}
 
 int launch_wsq_encode(const sq_params& p, const uint16_t* w, int64_t ldw, const float* hinv, const sq_wsq& out, hipStream_t st) {
   const int G = p.K / p.bank;
@@ -287,11 +480,17 @@ int launch_wsq_encode(const sq_params& p, const uint16_t* w, int64_t ldw, const 
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
-int launch_wsq_prepack(const sq_params& p, const sq_wsq& w, uint8_t* lo_clean, int8_t* hi_dense, hipStream_t st) {
+int launch_wsq_prepack(const sq_params& p, const sq_wsq& w, uint8_t* lo_clean, int8_t* hi_dense, float* s_lo_t, float* s_hi_t,
+                       hipStream_t st) {
   const int64_t total = static_cast<int64_t>(p.N) * (p.K / 32);
   const int vm = (-(1 << ((p.h_low ? p.h_low : 4) - 1))) & 0xF;
   hipLaunchKernelGGL(wsq_prepack_kernel, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st, p.N, p.K, p.bank,
                      p.topk, vm, w.lo, w.hi_val, lo_clean, hi_dense);
+  if (hipGetLastError() != hipSuccess) return SQ_ERR_LAUNCH;
+  const int G = p.K / p.bank, Npad = (p.N + 127) / 128 * 128;
+  const int64_t n_sc = static_cast<int64_t>(G) * Npad;
+  hipLaunchKernelGGL(wsq_scales_t_kernel, dim3(static_cast<unsigned>((n_sc + 255) / 256)), dim3(256), 0, st, p.N, G, Npad,
+                     w.scale_lo, w.scale_hi, s_lo_t, s_hi_t);
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
@@ -301,7 +500,28 @@ int launch_quantize_act(const sq_params& p, const uint16_t* x, int64_t ldx, int 
 }
 
 int launch_wsq_gemm(const sq_params& p, const int8_t* a8, const float* a_scale, const sq_wsq& w, const uint8_t* lo_clean,
-                    const int8_t* hi_dense, void* y, int64_t ldy, int32_t* acc_lo_dbg, int32_t* acc_hi_dbg, hipStream_t st) {
+                    const int8_t* hi_dense, const float* s_lo_t, const float* s_hi_t, void* y, int64_t ldy,
+                    int32_t* acc_lo_dbg, int32_t* acc_hi_dbg, hipStream_t st) {
+  if (!acc_lo_dbg && !acc_hi_dbg && p.M > 64) {  // the throughput kernel (the small kernel below also dumps the per-bank products)
+    Wsq2Args a;
+    a.M = p.M;
+    a.N = p.N;
+    a.K = p.K;
+    a.G = p.K / p.bank;
+    a.Npad = (p.N + 127) / 128 * 128;
+    a.bpb = p.bank / 64;
+    a.a8 = a8;
+    a.a_scale = a_scale;
+    a.lo_clean = lo_clean;
+    a.hi_dense = hi_dense;
+    a.s_lo_t = s_lo_t;
+    a.s_hi_t = s_hi_t;
+    a.y = y;
+    a.ldy = ldy;
+    a.out_bf16 = p.out_dtype == SQ_OUT_BF16;
+    hipLaunchKernelGGL(wsq_gemm2_kernel, dim3((p.N + 127) / 128, (p.M + 127) / 128), dim3(256), W2_NS * W2_STAGE, st, a);
+    return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+  }
   WsqGemmArgs g;
   g.M = p.M;
   g.N = p.N;

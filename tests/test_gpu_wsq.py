@@ -78,7 +78,8 @@ def test_activation_quantiser(M, K, bits):
 
 @pytest.mark.parametrize("M,K,N,bank,topk,h_high,h_low,bits", [(16, 256, 64, 64, 8, 8, 4, 8), (70, 512, 130, 64, 8, 8, 4, 8),
                                                               (33, 512, 200, 128, 16, 8, 4, 8), (5, 1024, 65, 64, 16, 8, 2, 8),
-                                                              (100, 256, 96, 64, 8, 4, 2, 4), (129, 384, 64, 128, 32, 8, 3, 8)])
+                                                              (100, 256, 96, 64, 8, 4, 2, 4), (129, 384, 64, 128, 32, 8, 3, 8),
+                                                              (300, 1024, 390, 64, 8, 8, 4, 8), (257, 512, 129, 128, 16, 8, 4, 8)])
 def test_layer_against_the_oracle(M, K, N, bank, topk, h_high, h_low, bits):
     _say(f"wsq linear M={M} K={K} N={N} bank={bank} topk={topk} ({h_high}/{h_low}) A{bits}")
     wb, xb, d = case(500 + M + K + N, M, K, N)
@@ -106,6 +107,12 @@ def test_layer_against_the_oracle(M, K, N, bank, topk, h_high, h_low, bits):
     err = np.abs(got.astype(np.float64) - prod.y32.astype(np.float64))
     assert (err <= 1e-6 * np.abs(prod.y32.astype(np.float64))).all()
     assert np.array_equal(got.view(np.uint32), prod.y32.view(np.uint32)), "fp32 outputs are expected to be bit-identical"
+    # without the per-bank dump (large shapes then take the throughput kernel): the same fp32 bits
+    y2 = Guarded(M * N * 4, torch.float32)
+    sq.sq_wsq_gemm(p, a8, sa, ws, pre.t, y2.t)
+    torch.cuda.synchronize()
+    y2.check()
+    assert np.array_equal(y2.host(np.uint32).reshape(M, N), prod.y32.view(np.uint32))
     # the fused entry point, bf16 output
     p16 = sq.params(M, K, N, bank, topk, out_dtype=sq.SQ_OUT_BF16, h_high=h_high, h_low=h_low)
     y16 = Guarded(M * N * 2, torch.int16)
