@@ -274,7 +274,7 @@ def sentinel_row_bytes(K, bank, topk, h_high, h_low):
 _wsq_mod = None
 
 
-def wsq():
+def wsq_module():
     """oracle.wsq, or -- only for the test that plants mistakes in it -- the copy named by SQ_ORACLE_WSQ_SRC."""
     global _wsq_mod
     if _wsq_mod is None:

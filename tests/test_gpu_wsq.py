@@ -12,7 +12,7 @@ from workloads import f32_to_bf16_bits, pack_int4
 from gpu_util import Guarded, dev
 
 pytestmark = pytest.mark.gpu
-W = oracle.wsq()
+W = oracle.wsq_module()
 
 
 def _say(msg):

@@ -13,7 +13,7 @@ import oracle
 from workloads import f32_to_bf16_bits, bf16_bits_to_f32
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-W = oracle.wsq()
+W = oracle.wsq_module()
 
 
 def bits_of(rows):
