@@ -454,7 +454,13 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / reps
+        # its bound: the per-bank fold, 5 vector instructions per output element and bank, against the chip's vector issue
+        # rate (256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-operations/s)
+        fold_ops = 5.0 * M * N * (K // pw.bank)
+        alu_peak = 256 * 4 * 16 * 2.4e9
         out["weights_sq_variant"] = {"ms_per_step": ms, "tops_2MNK": ops_eff / (ms * 1e-3) / 1e12, "bank": pw.bank, "topk": pw.topk,
+                                     "roofline": {"bound": "alu", "achieved": fold_ops / (ms * 1e-3) / 1e12, "peak": alu_peak / 1e12,
+                                                  "unit": "T lane-op/s", "frac": fold_ops / (ms * 1e-3) / alu_peak},
                                      "note": "sq_wsq_linear: per-token INT8 activations x SQ-format weights with per-(channel, bank) "
                                              "scales; bound by the per-bank fp32 fold (vector arithmetic), not by the matrix cores"}
 

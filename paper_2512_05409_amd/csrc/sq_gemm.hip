@@ -582,7 +582,10 @@ int launch_mode(const GemmArgs& g, hipStream_t st) {
 // instructions of step kt run: the per-step chain "barrier -> LDS read -> multiply -> barrier", which
 // otherwise bounds the streaming rate at N * 64 bytes per chain time, shrinks to the multiply.
 // A workgroup covers 64 output channels, so N/64 workgroups (two per compute unit) stream disjoint rows.
-// TI = number of 32-token blocks (1: M <= 32, 2: M <= 64).  Requires K % 128 == 0.
+// TI = number of 32-token blocks (1: M <= 32, 2: M <= 64).  Requires K % 128 == 0.  Only TI = 1 is dispatched: with
+// two token blocks (12 KB of activations per stage, one workgroup per compute unit, or shallower activation rings to
+// fit two) the kernel was slower than the generic 64 x 64 tile at every ring depth tried (67-70 us against 54 us at
+// 64 tokens on the 70B shape).
 template <int TI>
 struct SkinnyCfg {
   static constexpr int BM = 32 * TI;
