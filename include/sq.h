@@ -149,7 +149,9 @@ int sq_init(void);
 size_t sq_act_bytes(const sq_params *p, size_t *d_lo, size_t *hi_val, size_t *mask, size_t *scale);
 
 /* Bytes of device workspace sq_gemm needs when a->hi_dense is NULL (dynamic: the image of the
- * high part, M*K bytes; static: none -> returns 16 so that a valid pointer can always be passed). */
+ * high part, M*K bytes; static: none -> returns 16 so that a valid pointer can always be passed, except for
+ * M <= 32 with K % 128 == 0, where a workspace of M*K bytes lets sq_gemm run the weight-streaming decode kernel
+ * on the dense low part and an image of the high part; without it the generic tile runs). */
 size_t sq_gemm_workspace_bytes(const sq_params *p);
 
 /* Bytes of device workspace sq_linear needs: the encoded activations in the form sq_gemm multiplies

@@ -69,6 +69,10 @@ int check_params(const sq_params* p) {
 }
 
 inline int k_hi_of(const sq_params* p) { return (p->K / p->bank) * p->topk; }
+// Static mode with a handful of tokens: the layer is bound by streaming the weights once, which the
+// weight-streaming decode kernel does about twice as fast as the generic small tile; it takes the dense low part
+// and a zero-padded image of the high part (built from hi_val and the channel mask), i.e. the dynamic operands.
+inline bool static_decode(const sq_params* p) { return p->mode == SQ_STATIC && p->M <= 32 && p->K % 128 == 0; }
 inline size_t lo_compact_bytes(const sq_params* p) { return static_cast<size_t>(p->M) * ((p->K - k_hi_of(p)) / 2); }
 
 struct ActLayout {
@@ -130,7 +134,7 @@ size_t sq_act_bytes(const sq_params* p, size_t* d_lo, size_t* hi_val, size_t* ma
 
 size_t sq_gemm_workspace_bytes(const sq_params* p) {
   if (check_params(p) != SQ_OK) return 0;
-  if (p->mode != SQ_STATIC) return align_up(static_cast<size_t>(p->M) * p->K, 256);
+  if (p->mode != SQ_STATIC || static_decode(p)) return align_up(static_cast<size_t>(p->M) * p->K, 256);
   return 16;
 }
 
@@ -142,8 +146,9 @@ size_t sq_lo_compact_bytes(const sq_params* p) {
 size_t sq_linear_workspace_bytes(const sq_params* p) {
   if (check_params(p) != SQ_OK) return 0;
   const ActLayout l = act_layout(p);
-  const bool compact = p->mode == SQ_STATIC && sq::encode_static_gather_supports(*p);
+  const bool compact = p->mode == SQ_STATIC && sq::encode_static_gather_supports(*p) && !static_decode(p);
   size_t t = align_up(compact ? lo_compact_bytes(p) : l.d_lo, 256) + align_up(l.hi_val, 256) + 2 * align_up(l.scale, 256);
+  if (static_decode(p)) t += align_up(static_cast<size_t>(p->M) * p->K, 256);
   if (p->mode != SQ_STATIC) t += align_up(l.mask, 256) + align_up(static_cast<size_t>(p->M) * p->K, 256);
   return t;
 }
@@ -282,6 +287,11 @@ int sq_gemm(const sq_params* p, const sq_act* a, const sq_weight* w, void* y, in
       g.lda_hi_compact = p->K;
       g.w_hi = w->wq;
     }
+  } else if (static_decode(p) && a->d_lo && workspace && workspace_bytes >= sq_gemm_workspace_bytes(p) && aligned16(workspace)) {
+    // few tokens: the dynamic operands (see static_decode); optional -- without a workspace the generic tile runs
+    rc = sq::launch_expand_hi(*p, *a, static_cast<int8_t*>(workspace), st);
+    if (rc != SQ_OK) return rc;
+    g.a_hi_dense = static_cast<const int8_t*>(workspace);
   } else {
     g.K_hi = k_hi_of(p);
     g.a_hi_compact = a->hi_val;
@@ -310,7 +320,7 @@ int sq_linear(const sq_params* p, const uint16_t* x_bf16, int64_t ldx, const uin
   char* ws = static_cast<char*>(workspace);
   sq_act a;
   memset(&a, 0, sizeof a);
-  if (p->mode == SQ_STATIC && sq::encode_static_gather_supports(*p)) {
+  if (p->mode == SQ_STATIC && sq::encode_static_gather_supports(*p) && !static_decode(p)) {
     a.lo_compact = reinterpret_cast<uint8_t*>(ws);
     ws += align_up(lo_compact_bytes(p), 256);
   } else {
@@ -332,9 +342,15 @@ int sq_linear(const sq_params* p, const uint16_t* x_bf16, int64_t ldx, const uin
   } else {
     a.mask = const_cast<uint32_t*>(static_mask);
   }
+  void* gemm_ws = nullptr;
+  size_t gemm_ws_bytes = 0;
+  if (static_decode(p)) {
+    gemm_ws = ws;
+    gemm_ws_bytes = align_up(static_cast<size_t>(p->M) * p->K, 256);
+  }
   rc = sq_encode(p, x_bf16, ldx, static_mask, &a, stream);
   if (rc != SQ_OK) return rc;
-  return sq_gemm(p, &a, w, y, ldy, nullptr, nullptr, nullptr, 0, stream);
+  return sq_gemm(p, &a, w, y, ldy, nullptr, nullptr, gemm_ws, gemm_ws_bytes, stream);
 }
 
 size_t sq_storage_row_bytes(const sq_params* p) {

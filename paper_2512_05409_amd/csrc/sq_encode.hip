@@ -264,7 +264,7 @@ __global__ __launch_bounds__(MAXT) void encode_static_kernel(const uint16_t* __r
 __global__ __launch_bounds__(256) void expand_hi_kernel(const int8_t* __restrict__ hi_val,
                                                         const uint32_t* __restrict__ mask,
                                                         const uint8_t* __restrict__ d_lo, int64_t total, int K,
-                                                        int B, int KT, int8_t* __restrict__ out) {
+                                                        int B, int KT, int mask_rows, int8_t* __restrict__ out) {
   __shared__ uint4 stage[256 * 2];
   const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
   if (idx >= total) return;
@@ -273,7 +273,7 @@ __global__ __launch_bounds__(256) void expand_hi_kernel(const int8_t* __restrict
   const int wg = static_cast<int>(idx - row * wpr);
   const int wpb = B / 32;
   const int bank = wg / wpb;
-  const uint32_t* mrow = mask + row * wpr;
+  const uint32_t* mrow = mask + (mask_rows ? row * wpr : 0);  // mask_rows == 0: one channel mask for all rows (static)
   int rank = 0;
   for (int w = bank * wpb; w < wg; ++w) rank += __popc(mrow[w]);
   uint32_t word = mrow[wg];
@@ -481,7 +481,8 @@ int launch_expand_hi(const sq_params& p, const sq_act& a, int8_t* s_hi_dense, hi
   const int64_t total = static_cast<int64_t>(p.M) * (p.K / 32);
   const int64_t blocks = (total + 255) / 256;
   hipLaunchKernelGGL(expand_hi_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, a.hi_val, a.mask,
-                     p.mode == SQ_DYNAMIC_TIED ? a.d_lo : nullptr, total, p.K, p.bank, p.topk, s_hi_dense);
+                     p.mode == SQ_DYNAMIC_TIED ? a.d_lo : nullptr, total, p.K, p.bank, p.topk, p.mode == SQ_STATIC ? 0 : 1,
+                     s_hi_dense);
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 

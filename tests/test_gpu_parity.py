@@ -431,3 +431,34 @@ def test_static_long_rows(K, bank, topk):
     y.check()
     ws.check()
     assert np.array_equal(y.host(np.uint32).reshape(M, N), prod.y32.view(np.uint32))
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 1024, 200), (8, 2048, 130), (32, 1280, 96)])
+def test_static_decode_shapes_take_the_streaming_kernel(M, K, N):
+    """Static mode with at most 32 tokens: given a workspace, sq_gemm builds the image of the high part from
+    hi_val and the channel mask and runs the weight-streaming kernel on the dense low part: same accumulators,
+    same outputs as the oracle; without a workspace the generic tile gives the same bytes."""
+    _say(f"static decode M={M} K={K} N={N}")
+    bank, topk = 64, 8
+    bits, wq, sw = random_case(2700 + M + K + N, M, K, N, outliers=4)
+    mask = make_static_mask(K, bank, topk, seed=K + 7)
+    enc = oracle.encode(bits, bank, topk, static_mask=mask)
+    prod = oracle.gemm(enc, wq, sw)
+    p = sq.params(M, K, N, bank, topk, mode=sq.SQ_STATIC, out_dtype=sq.SQ_OUT_F32)
+    assert sq.sq_gemm_workspace_bytes(p) >= M * K
+    wqd, md = dev(wq), dev(mask)
+    pre = torch.empty(sq.sq_weight_prepack_bytes(p), dtype=torch.uint8, device="cuda")
+    sq.sq_weight_prepack(p, wqd, None, md, pre)
+    y, alo, ahi = run_gemm(p, enc, wq, sw, sq.SQ_OUT_F32, prepacked=pre, static_mask=mask)   # passes a workspace
+    assert np.array_equal(alo, prod.acc_lo) and np.array_equal(ahi, prod.acc_hi)
+    assert np.array_equal(y.view(np.uint32), prod.y32.view(np.uint32))
+    act = sq.Act(p, static_mask=md)
+    act.d_lo.copy_(dev(enc.d_lo).view(-1))
+    act.hi_val.copy_(dev(enc.hi_val).view(-1))
+    act.scale_lo.copy_(dev(enc.s_lo))
+    act.scale_hi.copy_(dev(enc.s_hi))
+    y2 = Guarded(M * N * 4, torch.float32)
+    sq.sq_gemm(p, act, sq.weight(wqd, dev(sw), pre), y2.t, None)
+    torch.cuda.synchronize()
+    y2.check()
+    assert np.array_equal(y2.host(np.uint32).reshape(M, N), prod.y32.view(np.uint32))
