@@ -52,7 +52,6 @@ struct StreamArgs {
   int lg;            // log2(min(G, 64)): lanes of a wave that belong to one row
   int wpr;           // waves per row (G / 64 when G > 64, else 1)
   int64_t units;     // ceil(M * G / 64)
-  int64_t banks;     // M * G
   uint8_t* d_lo;
   int8_t* hi_val;
   uint32_t* mask;
@@ -468,8 +467,7 @@ int launch_encode_stream(const sq_params& p, const uint16_t* x, int64_t ldx, con
   a.lgG = 0;
   while ((1 << a.lgG) < a.G) ++a.lgG;
   a.wpr = a.G > 64 ? a.G / 64 : 1;
-  a.banks = static_cast<int64_t>(p.M) * a.G;
-  a.units = (a.banks + 63) / 64;
+  a.units = (static_cast<int64_t>(p.M) * a.G + 63) / 64;
   a.d_lo = out.d_lo;
   a.hi_val = out.hi_val;
   a.mask = out.mask;

@@ -195,7 +195,6 @@ __global__ __launch_bounds__(256) void wsq_gemm_kernel(WsqGemmArgs g) {
   float f[16];
 #pragma unroll
   for (int q = 0; q < 16; ++q) f[q] = 0.0f;
-  const int n_col = min(n0 + 32 * wn + r, g.N - 1);
 
   for (int bank = 0; bank < g.G; ++bank) {
     // ---- stage the bank's operands (rows past the edge re-read the last row; never stored) ----
@@ -255,7 +254,6 @@ __global__ __launch_bounds__(256) void wsq_gemm_kernel(WsqGemmArgs g) {
     }
     __syncthreads();  // the tiles are overwritten by the next bank
   }
-  (void)n_col;
   // ---- epilogue ----
   const int n = n0 + 32 * wn + r;
 #pragma unroll
