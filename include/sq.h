@@ -209,7 +209,7 @@ int sq_gemm(const sq_params *p, const sq_act *a, const sq_weight *w, void *y, in
 
 /* Which of its kernels sq_gemm / sq_linear run for these parameters (static storage, never NULL):
  * "tile256x256" (SQ_DYNAMIC_TIED on shapes with at least 512 tiles of 256 x 256), "tile128x256" (workgroup tile of 128 tokens x 256 output channels; shapes with more than 128 such tiles),
- * "tile128x128" (fewer tiles), "tile64x64" (M <= 64), "stream32" (dynamic mode, M <= 32, K % 128 == 0: the
+ * "tile128x128" (fewer tiles), "tile64x64" (M <= 64), "tile64x128" (33 <= M <= 64 and N >= 25473), "stream32" (dynamic mode, M <= 32, K % 128 == 0: the
  * weight-streaming decode kernel), or "invalid".  Informational: tests use it to state which kernel a case covers. */
 const char *sq_gemm_variant(const sq_params *p);
 

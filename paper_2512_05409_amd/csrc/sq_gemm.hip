@@ -909,18 +909,26 @@ typedef Tile<128, 256> Big;   // matrix-core bound shapes
 typedef Tile<64, 64> Skinny;  // M <= 64 (decode): bound by streaming the INT4 weights once from HBM, so the
                               // tile is narrow in N to spread the weight rows over every compute unit
                               // (several small workgroups per unit keep enough loads in flight)
+typedef Tile<64, 128> SkinnyWide;  // the same for very wide layers: every workgroup re-reads the activation tile from
+                                   // L2 on each K step, and at 64 tokens that traffic (three times the weight
+                                   // stream) is what bounds the 64-wide tile; twice the channels per workgroup
+                                   // halves it (52 us against 55.5 us on the 70B shape) as long as the wider
+                                   // tiles still cover most compute units
 typedef Tile<128, 128> Mid;   // shapes with too few 128x256 tiles to occupy every compute unit
 typedef Tile<256, 256, false> Huge;  // single-product modes on large shapes: with one accumulator set a wave
                                      // holds 128 x 128 outputs, which halves the operand traffic and the
                                      // widening arithmetic per matrix instruction and doubles the matrix
                                      // instructions between two barriers to 64, as in the two-product loop
 
-enum Variant { V_BIG, V_MID, V_SMALL, V_STREAM, V_HUGE };
+enum Variant { V_BIG, V_MID, V_SMALL, V_STREAM, V_HUGE, V_SMALL_WIDE };
 
 // Which kernel a shape runs on.  dynamic: the call has the low operand and the zero-padded high image;
 // single: one product only (tied scales, plain W4A8).
 Variant pick_variant(int M, int N, int K, bool dynamic, bool single) {
-  if (M <= 64) return (dynamic && M <= 32 && K % KS == 0) ? V_STREAM : V_SMALL;
+  if (M <= 64) {
+    if (dynamic && M <= 32 && K % KS == 0) return V_STREAM;
+    return (M > 32 && (N + 127) / 128 >= 200) ? V_SMALL_WIDE : V_SMALL;
+  }
   const int64_t huge_tiles = static_cast<int64_t>((M + 255) / 256) * ((N + 255) / 256);
   if (single && huge_tiles >= kHugeMinTiles) return V_HUGE;
   const int64_t big_tiles = static_cast<int64_t>((M + 127) / 128) * ((N + 255) / 256);
@@ -940,6 +948,7 @@ int launch_for_mode(const GemmArgs& g, hipStream_t st, Variant v) {
   }
   if (v == V_BIG) return launch_mode<Big, MODE>(g, st);
   if (v == V_MID) return launch_mode<Mid, MODE>(g, st);
+  if (v == V_SMALL_WIDE) return launch_mode<SkinnyWide, MODE>(g, st);
   return launch_mode<Skinny, MODE>(g, st);
 }
 
@@ -953,7 +962,7 @@ int init_gemm_kernels() {
   if (e == hipSuccess) e = raise_lds_limit<T, 0>();          \
   if (e == hipSuccess) e = raise_lds_limit<T, 1>();          \
   if (e == hipSuccess) e = raise_lds_limit<T, 2>();
-  SQ_RAISE(Big) SQ_RAISE(Mid) SQ_RAISE(Skinny)
+  SQ_RAISE(Big) SQ_RAISE(Mid) SQ_RAISE(Skinny) SQ_RAISE(SkinnyWide)
 #undef SQ_RAISE
   if (e == hipSuccess) e = raise_lds_limit<Huge, 2>();
   if (e == hipSuccess)
@@ -968,6 +977,7 @@ const char* gemm_variant_name(int M, int N, int K, bool dynamic, bool single) {
     case V_BIG: return "tile128x256";
     case V_MID: return "tile128x128";
     case V_SMALL: return "tile64x64";
+    case V_SMALL_WIDE: return "tile64x128";
     default: return "stream32";
   }
 }

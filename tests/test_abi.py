@@ -178,7 +178,9 @@ def test_gemm_variant_names(L):
     assert sq.sq_gemm_variant(sq.params(4096, 4096, 22016)) == "tile128x256"      # 32 x 86 tiles
     assert sq.sq_gemm_variant(sq.params(1500, 320, 6100)) == "tile128x256"        # 12 x 24 tiles
     assert sq.sq_gemm_variant(sq.params(200, 1024, 300)) == "tile128x128"
-    assert sq.sq_gemm_variant(sq.params(64, 8192, 28672)) == "tile64x64"
+    assert sq.sq_gemm_variant(sq.params(64, 8192, 28672)) == "tile64x128"
+    assert sq.sq_gemm_variant(sq.params(64, 8192, 4096)) == "tile64x64"
+    assert sq.sq_gemm_variant(sq.params(20, 8192 + 64, 28672)) == "tile64x64"
     assert sq.sq_gemm_variant(sq.params(8, 8192, 28672)) == "stream32"
     assert sq.sq_gemm_variant(sq.params(8, 8192 + 64, 28672)) == "tile64x64"      # K % 128 != 0
     assert sq.sq_gemm_variant(sq.params(8, 8192, 28672, mode=sq.SQ_STATIC)) == "tile64x64"

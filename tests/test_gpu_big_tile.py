@@ -154,3 +154,25 @@ def test_tiny_magnitude_rows(M, N, variant):
     y, alo, ahi = run_gemm(p, enc, pack_int4(w), sw, sq.SQ_OUT_F32)
     assert np.array_equal(alo, prod.acc_lo) and np.array_equal(ahi, prod.acc_hi)
     assert np.array_equal(y.view(np.uint32), prod.y32.view(np.uint32))
+
+
+@pytest.mark.parametrize("mode", ["dynamic", "static"])
+@pytest.mark.parametrize("M,K,N", [(50, 256, 25700), (64, 384, 26000)])
+def test_wide_small_tile_every_element(M, K, N, mode):
+    """The 64 x 128 tile (33-64 tokens on very wide layers), every element, both accumulators."""
+    bank, topk = 64, 8
+    static = mode == "static"
+    if static and (K // bank * topk) % 32:
+        K = 512
+    p = sq.params(M, K, N, bank, topk, mode=sq.SQ_STATIC if static else sq.SQ_DYNAMIC, out_dtype=sq.SQ_OUT_F32)
+    assert sq.sq_gemm_variant(p) == "tile64x128"
+    _say(f"wide small tile {mode} M={M} K={K} N={N}")
+    bits, wq, sw = random_case(8000 + M + K + N, M, K, N, outliers=4)
+    if static:
+        mask = make_static_mask(K, bank, topk, seed=K + N)
+        enc = oracle.encode(bits, bank, topk, static_mask=mask)
+        pre = torch.empty(sq.sq_weight_prepack_bytes(p), dtype=torch.uint8, device="cuda")
+        sq.sq_weight_prepack(p, dev(wq), mask, dev(mask), pre)
+        check_all(p, enc, wq, sw, prepacked=pre, static_mask=mask)
+    else:
+        check_all(p, oracle.encode(bits, bank, topk), wq, sw)
