@@ -586,10 +586,10 @@ int launch_mode(const GemmArgs& g, hipStream_t st) {
 // two token blocks (12 KB of activations per stage, one workgroup per compute unit, or shallower activation rings to
 // fit two) the kernel was slower than the generic 64 x 64 tile at every ring depth tried (67-70 us against 54 us at
 // 64 tokens on the 70B shape).
-template <int TI>
+template <int TI, int TJ>
 struct SkinnyCfg {
   static constexpr int BM = 32 * TI;
-  static constexpr int BN = 64;
+  static constexpr int BN = 64 * TJ;           // TJ = 32-channel tiles per consumer wave (1 or 2)
   static constexpr int A_LO = 0;
   static constexpr int A_HI = BM * 64;
   static constexpr int A_STAGE = BM * 192;
@@ -607,21 +607,21 @@ struct SkinnyCfg {
 };
 
 // Weight loader wave: the four wave copies (64 rows x 64 bytes) of K step `step` into its ring stage.
-template <int TI>
-__device__ __forceinline__ void skinny_issue_w(const char* const (&src)[4], char* lds, int step) {
-  typedef SkinnyCfg<TI> C;
+template <int TI, int TJ>
+__device__ __forceinline__ void skinny_issue_w(const char* const (&src)[4 * TJ], char* lds, int step) {
+  typedef SkinnyCfg<TI, TJ> C;
   char* dst = lds + C::W_OFF + (step % C::W_STAGES) * C::W_STAGE;
 #pragma unroll
-  for (int q = 0; q < 4; ++q)
+  for (int q = 0; q < 4 * TJ; ++q)
     __builtin_amdgcn_global_load_lds(src[q] + step * 64, (lds_ptr_t)(dst + q * 1024), 16, 0, 0);
 }
 
 // Consumer waves: this wave's share of the activation tiles of K step `step`.
-template <int TI>
-__device__ __forceinline__ void skinny_issue_a(const char* const (&p_lo)[SkinnyCfg<TI>::N_LO],
-                                               const char* const (&p_hi)[SkinnyCfg<TI>::N_HI], char* lds, int step,
+template <int TI, int TJ>
+__device__ __forceinline__ void skinny_issue_a(const char* const (&p_lo)[SkinnyCfg<TI, TJ>::N_LO],
+                                               const char* const (&p_hi)[SkinnyCfg<TI, TJ>::N_HI], char* lds, int step,
                                                int wave) {
-  typedef SkinnyCfg<TI> C;
+  typedef SkinnyCfg<TI, TJ> C;
   char* dst = lds + (step % C::A_STAGES) * C::A_STAGE;
 #pragma unroll
   for (int i = 0; i < C::N_LO; ++i)
@@ -633,24 +633,25 @@ __device__ __forceinline__ void skinny_issue_a(const char* const (&p_lo)[SkinnyC
 
 // Operands of one K step of a consumer wave: packed weights of its 32 channels, packed low codes and
 // INT8 high codes of the tokens (two 64-channel halves each).
-template <int TI>
+template <int TI, int TJ>
 struct SkinnyOps {
-  v4u fw[2];
+  v4u fw[TJ][2];
   v4u fa[TI][2];
   v4i fh[TI][4];
 };
 
 // sa_idx / sw_idx: ring stages of the step's activation and weight tiles (compile-time constants in the
 // steady state, so that the reads differ only in their immediate offsets).
-template <int TI>
-__device__ __forceinline__ void skinny_fetch_at(SkinnyOps<TI>& o, const char* lds, int sa_idx, int sw_idx, int wave,
+template <int TI, int TJ>
+__device__ __forceinline__ void skinny_fetch_at(SkinnyOps<TI, TJ>& o, const char* lds, int sa_idx, int sw_idx, int wave,
                                                 int r, int h) {
-  typedef SkinnyCfg<TI> C;
+  typedef SkinnyCfg<TI, TJ> C;
   const char* sa = lds + sa_idx * C::A_STAGE;
   const char* sw = lds + C::W_OFF + sw_idx * C::W_STAGE;
 #pragma unroll
   for (int gq = 0; gq < 2; ++gq) {
-    o.fw[gq] = *reinterpret_cast<const v4u*>(sw + off4(wave * 32 + r, 2 * gq + h));
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) o.fw[j][gq] = *reinterpret_cast<const v4u*>(sw + off4((wave * TJ + j) * 32 + r, 2 * gq + h));
 #pragma unroll
     for (int i = 0; i < TI; ++i) {
       o.fa[i][gq] = *reinterpret_cast<const v4u*>(sa + C::A_LO + off4(i * 32 + r, 2 * gq + h));
@@ -660,33 +661,39 @@ __device__ __forceinline__ void skinny_fetch_at(SkinnyOps<TI>& o, const char* ld
   }
 }
 
-template <int TI>
-__device__ __forceinline__ void skinny_fetch(SkinnyOps<TI>& o, const char* lds, int step, int wave, int r, int h) {
-  skinny_fetch_at<TI>(o, lds, step % SkinnyCfg<TI>::A_STAGES, step % SkinnyCfg<TI>::W_STAGES, wave, r, h);
+template <int TI, int TJ>
+__device__ __forceinline__ void skinny_fetch(SkinnyOps<TI, TJ>& o, const char* lds, int step, int wave, int r, int h) {
+  skinny_fetch_at<TI, TJ>(o, lds, step % SkinnyCfg<TI, TJ>::A_STAGES, step % SkinnyCfg<TI, TJ>::W_STAGES, wave, r, h);
 }
 
-template <int TI>
-__device__ __forceinline__ void skinny_mma(const SkinnyOps<TI>& o, v16i (&acc_lo)[TI], v16i (&acc_hi)[TI]) {
+template <int TI, int TJ>
+__device__ __forceinline__ void skinny_mma(const SkinnyOps<TI, TJ>& o, v16i (&acc_lo)[TI][TJ], v16i (&acc_hi)[TI][TJ]) {
 #pragma unroll
   for (int gq = 0; gq < 2; ++gq)
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
-      const v4i bw = widen(o.fw[gq], s2);
+      v4i bw[TJ];
+#pragma unroll
+      for (int j = 0; j < TJ; ++j) bw[j] = widen(o.fw[j][gq], s2);
 #pragma unroll
       for (int i = 0; i < TI; ++i) {
-        acc_lo[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(widen(o.fa[i][gq], s2), bw, acc_lo[i], 0, 0, 0);
-        acc_hi[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(o.fh[i][2 * gq + s2], bw, acc_hi[i], 0, 0, 0);
+        const v4i alo = widen(o.fa[i][gq], s2);
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) {
+          acc_lo[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo, bw[j], acc_lo[i][j], 0, 0, 0);
+          acc_hi[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(o.fh[i][2 * gq + s2], bw[j], acc_hi[i][j], 0, 0, 0);
+        }
       }
     }
 }
 
 // Multiply one step, then join the step's barrier; `copied`: this step enqueued an activation copy, so
 // A_DIST - 2 younger ones may stay in flight, otherwise everything outstanding is waited for.
-template <int TI>
-__device__ __forceinline__ void pipeline_barrier_after(const SkinnyOps<TI>& cur, v16i (&acc_lo)[TI], v16i (&acc_hi)[TI],
+template <int TI, int TJ>
+__device__ __forceinline__ void pipeline_barrier_after(const SkinnyOps<TI, TJ>& cur, v16i (&acc_lo)[TI][TJ], v16i (&acc_hi)[TI][TJ],
                                                        bool copied) {
-  typedef SkinnyCfg<TI> C;
-  skinny_mma<TI>(cur, acc_lo, acc_hi);
+  typedef SkinnyCfg<TI, TJ> C;
+  skinny_mma<TI, TJ>(cur, acc_lo, acc_hi);
   if (copied) pipeline_barrier<(C::A_DIST - 2) * C::NA>();
   else pipeline_barrier<0>();
 }
@@ -699,12 +706,12 @@ __device__ __forceinline__ void pipeline_barrier_after(const SkinnyOps<TI>& cur,
 // LAST: the trip is the last one of the K loop (it ends at the last step): only its first steps still have a
 // copy to enqueue, its last step has no successor to fetch, and the barrier's allowance shrinks with the
 // copies that remain outstanding.
-template <int TI, int U, bool LAST = false>
-__device__ __forceinline__ void skinny_steady_step(const SkinnyOps<TI>& cur, SkinnyOps<TI>& nxt, const char* ub_lo,
-                                                   const char* ub_hi, const unsigned (&l_lo)[SkinnyCfg<TI>::N_LO],
-                                                   const unsigned (&l_hi)[SkinnyCfg<TI>::N_HI], char* lds, int wave,
-                                                   int r, int h, v16i (&acc_lo)[TI], v16i (&acc_hi)[TI]) {
-  typedef SkinnyCfg<TI> C;
+template <int TI, int TJ, int U, bool LAST = false>
+__device__ __forceinline__ void skinny_steady_step(const SkinnyOps<TI, TJ>& cur, SkinnyOps<TI, TJ>& nxt, const char* ub_lo,
+                                                   const char* ub_hi, const unsigned (&l_lo)[SkinnyCfg<TI, TJ>::N_LO],
+                                                   const unsigned (&l_hi)[SkinnyCfg<TI, TJ>::N_HI], char* lds, int wave,
+                                                   int r, int h, v16i (&acc_lo)[TI][TJ], v16i (&acc_hi)[TI][TJ]) {
+  typedef SkinnyCfg<TI, TJ> C;
   static_assert(8 % C::A_STAGES == 0 && 8 % C::W_STAGES == 0, "ring sizes must divide the trip length");
   constexpr bool FETCH = !LAST || U + 1 < 8;
   constexpr bool COPY = !LAST || U + C::A_DIST < 8;
@@ -712,7 +719,7 @@ __device__ __forceinline__ void skinny_steady_step(const SkinnyOps<TI>& cur, Ski
   // steady state, in the last trip only up to its last step (step kt+7)
   constexpr int YOUNGER = LAST ? (7 - (U + 2) > 0 ? 7 - (U + 2) : 0) : C::A_DIST - 2;
   constexpr int PENDING = (YOUNGER < C::A_DIST - 2 ? YOUNGER : C::A_DIST - 2) * C::NA;
-  if (FETCH) skinny_fetch_at<TI>(nxt, lds, (U + 1) % C::A_STAGES, (U + 1) % C::W_STAGES, wave, r, h);
+  if (FETCH) skinny_fetch_at<TI, TJ>(nxt, lds, (U + 1) % C::A_STAGES, (U + 1) % C::W_STAGES, wave, r, h);
   if (COPY) {
     char* dst = lds + ((U + C::A_DIST) % C::A_STAGES) * C::A_STAGE;
     const char* s_lo = ub_lo + (U + C::A_DIST) * 64;
@@ -724,13 +731,13 @@ __device__ __forceinline__ void skinny_steady_step(const SkinnyOps<TI>& cur, Ski
     for (int i = 0; i < C::N_HI; ++i)
       __builtin_amdgcn_global_load_lds(s_hi + l_hi[i], (lds_ptr_t)(dst + C::A_HI + (128 * i + 64 * wave) * 16), 16, 0, 0);
   }
-  skinny_mma<TI>(cur, acc_lo, acc_hi);
+  skinny_mma<TI, TJ>(cur, acc_lo, acc_hi);
   pipeline_barrier<PENDING>();  // the copies of steps <= kt + U + 2 have landed
 }
 
-template <int TI>
+template <int TI, int TJ>
 __global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
-  typedef SkinnyCfg<TI> C;
+  typedef SkinnyCfg<TI, TJ> C;
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -741,23 +748,23 @@ __global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
 
   if (wave == 2) {
     // ---- weight loader: 4 wave copies (64 rows x 64 bytes) per K step, W_AHEAD steps ahead ----
-    const char* src[4];
+    const char* src[4 * TJ];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int q = 0; q < 4 * TJ; ++q) {
       const int row = 16 * q + (lane >> 2);
       const int c = ((lane & 3) ^ (row >> 2)) & 3;
       src[q] = reinterpret_cast<const char*>(g.wq) + static_cast<int64_t>(min(n0 + row, g.N - 1)) * (g.K / 2) + c * 16;
     }
     // at barrier kt (the prologue barrier is kt = -1) the copies of steps <= kt+2 have landed
     const int pre = min(C::W_AHEAD, steps);
-    for (int s2 = 0; s2 < pre; ++s2) skinny_issue_w<TI>(src, lds, s2);
-    if (pre == C::W_AHEAD) pipeline_barrier<4 * (C::W_AHEAD - 2)>();
+    for (int s2 = 0; s2 < pre; ++s2) skinny_issue_w<TI, TJ>(src, lds, s2);
+    if (pre == C::W_AHEAD) pipeline_barrier<4 * TJ * (C::W_AHEAD - 2)>();
     else pipeline_barrier<0>();
     for (int kt = 0; kt < steps; ++kt) {
       if (kt + C::W_AHEAD < steps) {
         const int ahead = kt + W_AHEAD;
-        skinny_issue_w<TI>(src, lds, ahead);
-        pipeline_barrier<4 * (C::W_AHEAD - 2)>();  // five younger steps stay in flight
+        skinny_issue_w<TI, TJ>(src, lds, ahead);
+        pipeline_barrier<4 * TJ * (C::W_AHEAD - 2)>();  // five younger steps stay in flight
       } else {
         pipeline_barrier<0>();
       }
@@ -792,12 +799,15 @@ __global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
       slo[i][q] = g.s_lo[m];
       shi[i][q] = g.s_hi[m];
     }
-  const int n = n0 + wave * 32 + r;
-  const float sw = g.s_w[min(n, g.N - 1)];
+  float sw[TJ];
+#pragma unroll
+  for (int j = 0; j < TJ; ++j) sw[j] = g.s_w[min(n0 + (wave * TJ + j) * 32 + r, g.N - 1)];
 
-  v16i acc_lo[TI], acc_hi[TI];
+  v16i acc_lo[TI][TJ], acc_hi[TI][TJ];
 #pragma unroll
   for (int i = 0; i < TI; ++i)
+#pragma unroll
+  for (int j = 0; j < TJ; ++j)
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
       acc_lo[i][q] = 0;
@@ -810,7 +820,7 @@ __global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
   constexpr int D = C::A_DIST;
 #pragma unroll
   for (int s0 = 0; s0 < D; ++s0)
-    if (s0 < steps) skinny_issue_a<TI>(p_lo, p_hi, lds, s0, wave);
+    if (s0 < steps) skinny_issue_a<TI, TJ>(p_lo, p_hi, lds, s0, wave);
   if (steps >= D) pipeline_barrier<(D - 2) * C::NA>();
   else pipeline_barrier<0>();
   // Operands of one K step are fetched from LDS one step ahead of the matrix instructions that use them.
@@ -818,8 +828,8 @@ __global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
   // for the LDS reads of step kt+1 only after the matrix instructions of step kt have been issued) and no
   // address arithmetic: with few tokens a step is a handful of matrix instructions, so every other
   // instruction in it counts.
-  SkinnyOps<TI> o0, o1;
-  skinny_fetch<TI>(o0, lds, 0, wave, r, h);
+  SkinnyOps<TI, TJ> o0, o1;
+  skinny_fetch<TI, TJ>(o0, lds, 0, wave, r, h);
   int kt = 0;
   {
     // steady state: trips of eight steps with compile-time stage indices
@@ -831,45 +841,45 @@ __global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
     const char* ub_lo = reinterpret_cast<const char*>(g.a_lo);
     const char* ub_hi = reinterpret_cast<const char*>(g.a_hi_dense);
     for (; kt + 8 + D <= steps; kt += 8) {  // the copy of step kt + 7 + A_DIST is the last one a trip enqueues
-      skinny_steady_step<TI, 0>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
-      skinny_steady_step<TI, 1>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
-      skinny_steady_step<TI, 2>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
-      skinny_steady_step<TI, 3>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
-      skinny_steady_step<TI, 4>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
-      skinny_steady_step<TI, 5>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
-      skinny_steady_step<TI, 6>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
-      skinny_steady_step<TI, 7>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, TJ, 0>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, TJ, 1>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, TJ, 2>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, TJ, 3>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, TJ, 4>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, TJ, 5>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, TJ, 6>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, TJ, 7>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
       ub_lo += 8 * 64;
       ub_hi += 8 * 128;
     }
     if (steps - kt == 8) {  // exactly one trip left (K a multiple of 1024): the same code, winding down
-      skinny_steady_step<TI, 0, true>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
-      skinny_steady_step<TI, 1, true>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
-      skinny_steady_step<TI, 2, true>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
-      skinny_steady_step<TI, 3, true>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
-      skinny_steady_step<TI, 4, true>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
-      skinny_steady_step<TI, 5, true>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
-      skinny_steady_step<TI, 6, true>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
-      skinny_steady_step<TI, 7, true>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, TJ, 0, true>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, TJ, 1, true>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, TJ, 2, true>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, TJ, 3, true>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, TJ, 4, true>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, TJ, 5, true>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, TJ, 6, true>(o0, o1, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
+      skinny_steady_step<TI, TJ, 7, true>(o1, o0, ub_lo, ub_hi, l_lo, l_hi, lds, wave, r, h, acc_lo, acc_hi);
       kt += 8;
     }
   }
   // the remaining steps (fewer than 8 + A_DIST): stage indices and addresses computed at run time
   while (kt < steps) {
-    if (kt + 1 < steps) skinny_fetch<TI>(o1, lds, kt + 1, wave, r, h);
+    if (kt + 1 < steps) skinny_fetch<TI, TJ>(o1, lds, kt + 1, wave, r, h);
     if (kt + D < steps) {
-      skinny_issue_a<TI>(p_lo, p_hi, lds, kt + D, wave);
-      pipeline_barrier_after<TI>(o0, acc_lo, acc_hi, true);
+      skinny_issue_a<TI, TJ>(p_lo, p_hi, lds, kt + D, wave);
+      pipeline_barrier_after<TI, TJ>(o0, acc_lo, acc_hi, true);
     } else {
-      pipeline_barrier_after<TI>(o0, acc_lo, acc_hi, false);
+      pipeline_barrier_after<TI, TJ>(o0, acc_lo, acc_hi, false);
     }
     if (++kt >= steps) break;
-    if (kt + 1 < steps) skinny_fetch<TI>(o0, lds, kt + 1, wave, r, h);
+    if (kt + 1 < steps) skinny_fetch<TI, TJ>(o0, lds, kt + 1, wave, r, h);
     if (kt + D < steps) {
-      skinny_issue_a<TI>(p_lo, p_hi, lds, kt + D, wave);
-      pipeline_barrier_after<TI>(o1, acc_lo, acc_hi, true);
+      skinny_issue_a<TI, TJ>(p_lo, p_hi, lds, kt + D, wave);
+      pipeline_barrier_after<TI, TJ>(o1, acc_lo, acc_hi, true);
     } else {
-      pipeline_barrier_after<TI>(o1, acc_lo, acc_hi, false);
+      pipeline_barrier_after<TI, TJ>(o1, acc_lo, acc_hi, false);
     }
     ++kt;
   }
@@ -895,10 +905,10 @@ __global__ __launch_bounds__(192) void gemm_skinny_kernel(GemmArgs g) {
   }
 }
 
-template <int TI>
+template <int TI, int TJ>
 int launch_skinny(const GemmArgs& g, hipStream_t st) {
-  typedef SkinnyCfg<TI> C;
-  hipLaunchKernelGGL((gemm_skinny_kernel<TI>), dim3((g.N + C::BN - 1) / C::BN), dim3(C::THREADS), C::LDS_BYTES, st, g);
+  typedef SkinnyCfg<TI, TJ> C;
+  hipLaunchKernelGGL((gemm_skinny_kernel<TI, TJ>), dim3((g.N + C::BN - 1) / C::BN), dim3(C::THREADS), C::LDS_BYTES, st, g);
   return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
